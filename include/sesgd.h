@@ -1,0 +1,136 @@
+/*
+ * sesgd.h -- C ABI of the Shuffle-Exchange SGD (SESGD) step library for AMD gfx950.
+ *
+ * The library simulates n logical data-parallel workers as n rows of one packed,
+ * multi-layer buffer in a single GPU's memory and performs, per training iteration,
+ *   (1) the regrouping of the workers into n/group_size equal groups
+ *       (Sec. 3.1 "Shuffle-Exchange"; Algorithm 1, the two regrouping steps),
+ *   (2) each worker's local SGD/momentum step followed by the average of the locally
+ *       updated parameters inside the worker's group
+ *       (Sec. 3.2 "Gradient Correction", the SESGD update equation; Algorithm 1),
+ *   (3) as a baseline, the fully synchronous Ring-SGD/DSGD step
+ *       (Sec. 3.2, the DSGD equation; Sec. 2.2 for the all-reduce it stands for).
+ *
+ * Conventions shared by all calls
+ *   - Plain C, no exceptions, no torch types.  Every function returns SE_OK (0) or a
+ *     negative SE_ERR_* code; on error nothing has been written or launched.
+ *   - "device" pointers are HIP device addresses owned by the caller; "host" pointers are
+ *     ordinary host memory.  The library never frees or keeps a caller's pointer.
+ *   - Replica layout: params, grads and momentum each hold n rows; row i (worker i)
+ *     starts at base + i*pitch elements, pitch = layer_offsets[num_layers].  A caller who
+ *     wants padded rows appends a dummy last layer so that the last offset is the pitch.
+ *   - layer_offsets is a HOST array of num_layers+1 non-decreasing element offsets with
+ *     layer_offsets[0] == 0.  Groups are drawn once per iteration for the whole model, and
+ *     the update is elementwise, so the result does not depend on where the layer
+ *     boundaries fall; the offsets define the pitch and are validated.
+ *   - The three buffers must not overlap.  params and momentum are updated in place.
+ *   - stream is a hipStream_t passed as void* (NULL = the default stream).  se_step and
+ *     se_ring_step only enqueue work on it and return without synchronising.
+ *   - fp32 arithmetic, round-to-nearest-even, denormals kept, with this fixed order per
+ *     element e and group with members j_0 < j_1 < ... (ascending worker id):
+ *         v'_j   = fma(mu, v_j, g_j)            (g_j if momentum == NULL)
+ *         xhat_j = fma(-lr, v'_j, x_j)
+ *         s      = xhat_{j_0} + xhat_{j_1} + ...   left to right
+ *         x_j    = s * (1.0f / (float)group_size)  for every member;   v_j = v'_j
+ *     NaN/Inf propagate.
+ */
+#ifndef SESGD_H
+#define SESGD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SE_OK                  0
+#define SE_ERR_ARG           (-1)  /* n<1, group_size<1, group_size>n, iter<0, num_layers<0 */
+#define SE_ERR_DIVISIBILITY  (-2)  /* n % group_size != 0: the paper defines equal groups only */
+#define SE_ERR_NULL          (-3)  /* a required pointer is NULL */
+#define SE_ERR_LAYOUT        (-4)  /* offsets not monotone, offsets[0]!=0, buffers overlap, misaligned */
+#define SE_ERR_UNSUPPORTED   (-5)  /* n > SE_MAX_WORKERS, or pitch >= 2^30 elements */
+#define SE_ERR_HIP           (-6)  /* a HIP call failed; se_last_error() has the HIP string */
+
+#define SE_MAX_WORKERS 64          /* one wavefront lane per worker in the plan generator */
+
+/*
+ * Regrouping for iteration `iter` (Sec. 3.1; Algorithm 1: "randomly generate new groups
+ * depending on the seed", "enter a new group").  Every worker derives the same partition
+ * from the shared seed (se_set_seed), so no message is exchanged.  The partition is a
+ * pure function of (seed, n, iter): workers are ordered by a 32-bit hash of
+ * (seed, iter, n, worker id), ties by id, and the order is cut into blocks of group_size.
+ *   group_of [host, n ints, out]           group index in [0, n/group_size) of each worker
+ *   members  [host, n ints, out, may be NULL] group-major; members[g*group_size + r] is the
+ *                                           r-th smallest worker id of group g
+ * Runs the device generator on the current device, synchronously (default stream).
+ */
+int se_plan(int n, int group_size, int64_t iter, int32_t *group_of, int32_t *members);
+
+/* Same, asynchronous: both outputs are DEVICE arrays of n ints written on `stream`
+ * (members_dev may be NULL).  Allocates nothing. */
+int se_plan_device(int n, int group_size, int64_t iter, int32_t *group_of_dev,
+                   int32_t *members_dev, void *stream);
+
+/*
+ * One SESGD iteration over all layers in one launch (Sec. 3.2, the SESGD update equation;
+ * Algorithm 1 loop body with the minibatch gradient already formed in `grads`).
+ *   params   [device, n*pitch fp32, in/out]
+ *   grads    [device, n*pitch fp32, in]
+ *   momentum [device, n*pitch fp32, in/out]  may be NULL iff mu == 0: plain SGD, no
+ *                                            momentum bytes are touched.  One buffer per
+ *                                            worker; it is never averaged.
+ *   group_size == 1 is local SGD without averaging; group_size == n is the full average.
+ */
+int se_step(float *params, const float *grads, float *momentum,
+            const int64_t *layer_offsets, int num_layers,
+            int n, int group_size, int64_t iter, float lr, float mu, void *stream);
+
+/* Same with gradients stored as bfloat16 bit patterns (uint16); widening to fp32 is exact. */
+int se_step_bf16g(float *params, const uint16_t *grads_bf16, float *momentum,
+                  const int64_t *layer_offsets, int num_layers,
+                  int n, int group_size, int64_t iter, float lr, float mu, void *stream);
+
+/*
+ * One Ring-SGD / DSGD iteration (Sec. 3.2, the DSGD equation): the mean gradient over all
+ * n workers, gbar = (g_0 + g_1 + ... + g_{n-1}) * (1.0f/(float)n) left to right, then on
+ * every worker v_i = fma(mu, v_i, gbar) (gbar if momentum == NULL), x_i = fma(-lr, v_i, x_i).
+ * Same buffers and layout as se_step.
+ */
+int se_ring_step(float *params, const float *grads, float *momentum,
+                 const int64_t *layer_offsets, int num_layers,
+                 int n, float lr, float mu, void *stream);
+
+int se_ring_step_bf16g(float *params, const uint16_t *grads_bf16, float *momentum,
+                       const int64_t *layer_offsets, int num_layers,
+                       int n, float lr, float mu, void *stream);
+
+/* The shared random seed of Algorithm 1 (process-wide, default 0).  Read at call time by
+ * se_plan, se_plan_device and se_step. */
+int      se_set_seed(uint64_t seed);
+uint64_t se_get_seed(void);
+
+/* Recommended row pitch for P elements: P rounded up to a multiple of 64 elements, so every
+ * row starts 256-byte aligned and the 128-bit path is taken.  Returns -1 for P < 0. */
+int64_t se_pitch(int64_t P);
+
+/* Bytes the method itself moves per call (reads + writes of params, grads, momentum),
+ * the numerator of the achieved-bandwidth figure: n*pitch*(8 + grad bytes + 8 if momentum). */
+int64_t se_step_bytes(int64_t pitch, int n, int grad_elem_bytes, int has_momentum);
+
+/* Launch-shape knobs for measurement sweeps; results never depend on them.
+ *   "grid_blocks_per_cu"  blocks per compute unit of the grid-stride launch (0 = one block per tile)
+ *   "group_major"         1: all tiles of group 0 first; 0: the groups of one tile side by side
+ *   "nontemporal"         bit 0: non-temporal loads, bit 1: non-temporal stores
+ * Returns SE_ERR_ARG for an unknown name or a value out of range. */
+int se_set_tuning(const char *name, int value);
+int se_get_tuning(const char *name);
+
+/* Static description of an error code; for SE_ERR_HIP, se_last_error() returns the text of
+ * the failing HIP call of the calling thread's most recent failure. */
+const char *se_strerror(int code);
+const char *se_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SESGD_H */

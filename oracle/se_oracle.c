@@ -1,0 +1,220 @@
+/*
+ * CPU oracle for the Shuffle-Exchange SGD (SESGD) step.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, plain definition of what the GPU library computes.  It is
+ * used by the tests, by the smoke check and by the benchmark's CPU-baseline leg, and
+ * by nothing else.  It shares no code, header, table or constant generator with the
+ * HIP sources and must never be linked into, or called from, the product path.
+ *
+ * Every function evaluates the paper's definition directly, one element at a time,
+ * in fp32 with a fixed evaluation order, round-to-nearest-even, no contraction other
+ * than the two explicit fmaf() calls, no flush-to-zero.  Build with
+ *     gcc -O2 -ffp-contract=off -shared -fPIC
+ *
+ * What follows the paper and what is this build's convention:
+ *   - Regrouping (Sec. 3.1 "Shuffle-Exchange"; Algorithm 1, the "randomly generate new
+ *     groups depending on the seed" step): the paper fixes only that every worker derives
+ *     the same random partition into k equal groups from a shared seed, and (appendix,
+ *     proof of the lemma) that two workers are separated with probability
+ *     n(k-1)/(k(n-1)), i.e. the partition is uniform.  The hash below that realises it
+ *     is a convention of this build; its bits are not pinned by the paper.
+ *   - Update (Sec. 3.2 "Gradient Correction", the SESGD update equation; Algorithm 1):
+ *     local step into x-hat, then the mean of x-hat over the worker's group.  The factor
+ *     k/n of the equation is 1/group_size.
+ *   - Momentum (Sec. 4.1 hyper-parameters: "0.9"): v <- mu*v + g, x-hat = x - lr*v,
+ *     one buffer per worker, never averaged (Algorithm 1 all-reduces x-hat only).
+ *   - Baseline (Sec. 3.2, the DSGD equation): mean gradient over all n workers, the same
+ *     update on every worker.
+ *   - Summation order: members in ascending worker id, left to right (paper is silent).
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+#define ORACLE_OK 0
+#define ORACLE_ERR_ARG (-1)
+#define ORACLE_ERR_DIVISIBILITY (-2)
+#define ORACLE_MAX_N 4096
+
+/* 32-bit finaliser: xor-shift / odd-multiply rounds.  Multipliers are the first 32
+ * fractional bits of sqrt(2) and sqrt(3); the additive constant is floor(2^32/phi). */
+static uint32_t mix32(uint32_t z)
+{
+    z ^= z >> 16;
+    z *= 0x6A09E667u;
+    z ^= z >> 15;
+    z *= 0xBB67AE85u;
+    z ^= z >> 16;
+    return z;
+}
+
+/* Sort key of worker i at iteration iter: absorb the six words
+ * (seed low, seed high, iter low, iter high, n, i) one after the other. */
+uint32_t oracle_key(uint64_t seed, int64_t iter, int n, int i)
+{
+    const uint32_t golden = 0x9E3779B9u;
+    uint64_t t = (uint64_t)iter;
+    uint32_t w[6];
+    uint32_t h = golden;
+    int q;
+    w[0] = (uint32_t)(seed & 0xFFFFFFFFu);
+    w[1] = (uint32_t)(seed >> 32);
+    w[2] = (uint32_t)(t & 0xFFFFFFFFu);
+    w[3] = (uint32_t)(t >> 32);
+    w[4] = (uint32_t)n;
+    w[5] = (uint32_t)i;
+    for (q = 0; q < 6; ++q)
+        h = mix32((h ^ w[q]) + golden);
+    return h;
+}
+
+/*
+ * Regrouping for one iteration (Sec. 3.1; Algorithm 1).
+ *   rank[i]     = number of workers whose (key, id) pair is lexicographically smaller
+ *   group_of[i] = rank[i] / m
+ *   members[g*m + r] = r-th smallest worker id of group g
+ * keys, rank, members may be NULL.  Returns 0, or a negative error.
+ */
+int oracle_plan(uint64_t seed, int n, int m, int64_t iter,
+                uint32_t *keys, int32_t *rank, int32_t *group_of, int32_t *members)
+{
+    uint32_t key_buf[ORACLE_MAX_N];
+    int i, j;
+    if (n < 1 || n > ORACLE_MAX_N || m < 1 || m > n || iter < 0 || group_of == NULL)
+        return ORACLE_ERR_ARG;
+    if (n % m != 0)
+        return ORACLE_ERR_DIVISIBILITY;
+    for (i = 0; i < n; ++i)
+        key_buf[i] = oracle_key(seed, iter, n, i);
+    for (i = 0; i < n; ++i) {
+        int below = 0;
+        for (j = 0; j < n; ++j) {
+            if (key_buf[j] < key_buf[i] || (key_buf[j] == key_buf[i] && j < i))
+                ++below;
+        }
+        if (keys) keys[i] = key_buf[i];
+        if (rank) rank[i] = below;
+        group_of[i] = below / m;
+    }
+    if (members) {
+        int k = n / m, g;
+        for (g = 0; g < k; ++g) {
+            int r = 0;
+            for (i = 0; i < n; ++i)          /* ascending worker id */
+                if (group_of[i] == g)
+                    members[g * m + r++] = i;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* bf16 -> fp32 is exact: the 16 bits are the high half of the fp32 pattern. */
+static float bf16_to_f32(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+static float load_grad(const void *grads, int grads_are_bf16, int64_t idx)
+{
+    if (grads_are_bf16)
+        return bf16_to_f32(((const uint16_t *)grads)[idx]);
+    return ((const float *)grads)[idx];
+}
+
+/*
+ * One SESGD iteration on columns [col_begin, col_end) of n replica rows of length
+ * `pitch` (Sec. 3.2, the SESGD update equation; Algorithm 1 body).
+ *
+ *   for every group G of this iteration's plan, every column e:
+ *     for members j of G in ascending id:
+ *        v'   = momentum ? fmaf(mu, momentum[j][e], g[j][e]) : g[j][e]
+ *        xhat = fmaf(-lr, v', params[j][e])
+ *        s    = (first member) ? xhat : s + xhat
+ *     mean = s * (1.0f / (float)m)
+ *     params[j][e] = mean for every member j;  momentum[j][e] = v'
+ *
+ * momentum may be NULL (plain SGD; mu is then ignored).
+ */
+int oracle_step(float *params, const void *grads, int grads_are_bf16, float *momentum,
+                int64_t pitch, int64_t col_begin, int64_t col_end,
+                int n, int m, uint64_t seed, int64_t iter, float lr, float mu)
+{
+    int32_t group_of[ORACLE_MAX_N];
+    int32_t members[ORACLE_MAX_N];
+    int rc, g, r, k;
+    int64_t e;
+    float inv_m;
+    if (params == NULL || grads == NULL || pitch < 0 || col_begin < 0 ||
+        col_end < col_begin || col_end > pitch)
+        return ORACLE_ERR_ARG;
+    rc = oracle_plan(seed, n, m, iter, NULL, NULL, group_of, members);
+    if (rc != ORACLE_OK)
+        return rc;
+    k = n / m;
+    inv_m = 1.0f / (float)m;
+    for (g = 0; g < k; ++g) {
+        const int32_t *mem = members + (size_t)g * m;
+        for (e = col_begin; e < col_end; ++e) {
+            float s = 0.0f, mean;
+            for (r = 0; r < m; ++r) {
+                int64_t idx = (int64_t)mem[r] * pitch + e;
+                float gg = load_grad(grads, grads_are_bf16, idx);
+                float vn, xhat;
+                if (momentum) {
+                    vn = fmaf(mu, momentum[idx], gg);
+                    momentum[idx] = vn;
+                } else {
+                    vn = gg;
+                }
+                xhat = fmaf(-lr, vn, params[idx]);
+                s = (r == 0) ? xhat : s + xhat;
+            }
+            mean = s * inv_m;
+            for (r = 0; r < m; ++r)
+                params[(int64_t)mem[r] * pitch + e] = mean;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * One Ring-SGD (fully synchronous DSGD) iteration (Sec. 3.2, the DSGD equation):
+ *   gbar = (g[0][e] + g[1][e] + ... + g[n-1][e]) * (1.0f / (float)n)   (left to right)
+ *   v'   = momentum ? fmaf(mu, momentum[i][e], gbar) : gbar
+ *   params[i][e] = fmaf(-lr, v', params[i][e])          for every worker i
+ */
+int oracle_ring_step(float *params, const void *grads, int grads_are_bf16, float *momentum,
+                     int64_t pitch, int64_t col_begin, int64_t col_end,
+                     int n, float lr, float mu)
+{
+    int i;
+    int64_t e;
+    float inv_n;
+    if (params == NULL || grads == NULL || n < 1 || pitch < 0 || col_begin < 0 ||
+        col_end < col_begin || col_end > pitch)
+        return ORACLE_ERR_ARG;
+    inv_n = 1.0f / (float)n;
+    for (e = col_begin; e < col_end; ++e) {
+        float s = load_grad(grads, grads_are_bf16, e);
+        float gbar;
+        for (i = 1; i < n; ++i)
+            s = s + load_grad(grads, grads_are_bf16, (int64_t)i * pitch + e);
+        gbar = s * inv_n;
+        for (i = 0; i < n; ++i) {
+            int64_t idx = (int64_t)i * pitch + e;
+            float vn;
+            if (momentum) {
+                vn = fmaf(mu, momentum[idx], gbar);
+                momentum[idx] = vn;
+            } else {
+                vn = gbar;
+            }
+            params[idx] = fmaf(-lr, vn, params[idx]);
+        }
+    }
+    return ORACLE_OK;
+}
