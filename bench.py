@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the SESGD hot path on one MI355X.
+
+A step is one pass of the whole hot path over the packed multi-layer buffer: regrouping,
+local SGD/momentum update, group average and write-back for all n workers and all layers,
+one `se_step` launch.  Inputs (params, momentum, a small pool of gradient buffers) are
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X published peak HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="resnet50")
+    ap.add_argument("--grad-pool", type=int, default=4, help="distinct gradient buffers cycled through")
+    ap.add_argument("--no-pad", action="store_true", help="use pitch = P instead of se_pitch(P)")
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-ring", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=3.0, help="target CPU time per oracle leg")
+    ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE")
+    return ap.parse_args()
+
+
+def timed_steps(launch, steps, warmup, torch):
+    """Runs warmup + steps launches on the current stream; returns (wall seconds for the
+    timed steps, mean seconds per launch from stream events)."""
+    stream = torch.cuda.current_stream()
+    for t in range(warmup):
+        launch(t, stream)
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for t in range(warmup, warmup + steps):
+        launch(t, stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, ev0.elapsed_time(ev1) * 1e-3 / steps
+
+
+def cpu_baseline(w, pitch, target_seconds):
+    """The oracle as it stands, on a column slice of the same workload, timed on this host:
+    once from a single thread, once from one thread per available core on disjoint column
+    blocks.  Returns steps/s extrapolated linearly in columns (columns are independent)."""
+    import numpy as np
+    import oracle
+    from paper_2007_00433_amd import workloads as wl
+
+    cores = len(os.sched_getaffinity(0))
+    n, m = w.n, w.group_size
+
+    def make(cols):
+        x = wl.host_params(n, cols, w.param_std, 0)
+        v = np.zeros_like(x)
+        g = wl.host_grads(n, cols, w.grad_std, 0, 0, w.grad_dtype)
+        return x, v, g
+
+    # calibrate the single-thread rate on a small slice, then size the samples
+    probe = int(min(pitch, 1 << 20))                                # beyond the host caches
+    x, v, g = make(probe)
+    t0 = time.perf_counter()
+    oracle.step(x, g, v, m, 0, w.lr, w.mu)
+    rate = probe / max(time.perf_counter() - t0, 1e-6)              # columns per second
+    cols1 = int(min(pitch, max(1 << 16, rate * target_seconds / 2)))
+    x, v, g = make(cols1)
+    t0 = time.perf_counter()
+    for t in range(2):
+        oracle.step(x, g, v, m, t, w.lr, w.mu)
+    single = (time.perf_counter() - t0) / 2 * (pitch / cols1)       # seconds per full step
+    colsN = int(min(pitch, cols1 * max(1, cores // 2)))
+    x, v, g = make(colsN)
+    t0 = time.perf_counter()
+    for t in range(2):
+        oracle.step_threaded(x, g, v, m, t, w.lr, w.mu, threads=cores)
+    multi = (time.perf_counter() - t0) / 2 * (pitch / colsN)
+    return {
+        "value": round(1.0 / multi, 4), "unit": "steps/s", "cores": cores, "kind": "oracle",
+        "sample": f"oracle_step on the first {colsN} of {pitch} columns of all {n} rows, 2 steps, "
+                  f"{cores} threads on disjoint column blocks; extrapolated linearly in columns",
+        "single_thread_value": round(1.0 / single, 4),
+        "single_thread_sample": f"first {cols1} columns, 2 steps, 1 thread",
+        "gbytes_per_s": round(n * pitch * (16 + w.grad_bytes) / multi / 1e9, 2),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (all {args.gpus} requested ranks would "
+              "need a second device); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2007_00433_amd import binding as se
+    from paper_2007_00433_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    for kv in args.tune:
+        name, value = kv.split("=")
+        se.se_set_tuning(name, int(value))
+
+    w = wl.WORKLOADS[args.workload]
+    n, m, P = w.n, w.group_size, w.P
+    pitch = P if args.no_pad else se.se_pitch(P)
+    offs = w.layer_offsets(pitch)
+    bf16 = w.grad_dtype == "bf16"
+    step_fn = se.se_step_bf16g if bf16 else se.se_step
+    ring_fn = se.se_ring_step_bf16g if bf16 else se.se_ring_step
+
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(0)
+    x = torch.zeros(n, pitch, device="cuda")
+    x[:, :P] = torch.randn(P, device="cuda", generator=gen) * w.param_std
+    v = torch.zeros(n, pitch, device="cuda")
+    pool = []
+    for _ in range(max(1, args.grad_pool)):
+        g = torch.zeros(n, pitch, device="cuda", dtype=torch.bfloat16 if bf16 else torch.float32)
+        for i in range(n):
+            g[i, :P] = (torch.randn(P, device="cuda", generator=gen) * w.grad_std).to(g.dtype)
+        pool.append(g)
+    torch.cuda.synchronize()
+
+    def launch_step(t, stream):
+        step_fn(x, pool[t % len(pool)], v, offs, n, m, t, w.lr, w.mu, stream)
+
+    def launch_ring(t, stream):
+        ring_fn(x, pool[t % len(pool)], v, offs, n, w.lr, w.mu, stream)
+
+    wall, per_launch = timed_steps(launch_step, args.steps, args.warmup, torch)
+    bytes_per_launch = se.se_step_bytes(pitch, n, w.grad_bytes, True)
+    achieved = bytes_per_launch / per_launch / 1e9
+
+    out = {
+        "metric": "SESGD steps/sec and achieved HBM GB/s (% of peak), n=16 ResNet-50-shaped"
+                  if args.workload == "resnet50" else f"SESGD steps/sec, {args.workload}",
+        "value": round(args.steps / wall, 3),
+        "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall / args.steps * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if not bf16 else "f32 (bf16 gradient storage)",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}-shaped packed buffer", "n_workers": n,
+                   "group_size": m, "tensors": len(w.sizes), "params_per_worker": P,
+                   "pitch": pitch, "lr": w.lr, "momentum": w.mu, "grad_dtype": w.grad_dtype,
+                   "grad_buffers_cycled": len(pool),
+                   "tuning": {k: se.se_get_tuning(k) for k in
+                              ("grid_blocks_per_cu", "group_major", "nontemporal")}},
+        "roofline": {"bound": "hbm", "kernel": "se_step_kernel", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": None, "bytes_per_launch": bytes_per_launch,
+                     "avg_launch_ms": round(per_launch * 1e3, 5)},
+    }
+    if not args.skip_ring:
+        rwall, rper = timed_steps(launch_ring, args.steps, args.warmup, torch)
+        out["ring_baseline"] = {"value": round(args.steps / rwall, 3), "unit": "steps/s",
+                                "achieved_gbs": round(bytes_per_launch / rper / 1e9, 1),
+                                "frac": round(bytes_per_launch / rper / 1e9 / HBM_PEAK_GBS, 4)}
+    if not args.skip_cpu_baseline:
+        del pool, x, v
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(w, pitch, args.cpu_seconds)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,204 @@
+"""ctypes binding of libsesgd.so: the same names as include/sesgd.h, argument marshalling
+only.  Buffers are torch tensors (device memory) or raw integer addresses; nothing here
+computes.  Importing this module without a built library raises: there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libsesgd.so")
+
+SE_OK = 0
+SE_ERR_ARG = -1
+SE_ERR_DIVISIBILITY = -2
+SE_ERR_NULL = -3
+SE_ERR_LAYOUT = -4
+SE_ERR_UNSUPPORTED = -5
+SE_ERR_HIP = -6
+SE_MAX_WORKERS = 64
+
+EXPORTS = ("se_plan", "se_plan_device", "se_step", "se_step_bf16g", "se_ring_step",
+           "se_ring_step_bf16g", "se_set_seed", "se_get_seed", "se_pitch", "se_step_bytes",
+           "se_set_tuning", "se_get_tuning", "se_strerror", "se_last_error")
+
+
+class SesgdError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"sesgd error {code}: {text}")
+        self.code = code
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2007_00433_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i32, i64, u64 = ctypes.c_int, ctypes.c_int64, ctypes.c_uint64
+    vp, f32, cp = ctypes.c_void_p, ctypes.c_float, ctypes.c_char_p
+    lib.se_plan.restype = i32
+    lib.se_plan.argtypes = [i32, i32, i64, vp, vp]
+    lib.se_plan_device.restype = i32
+    lib.se_plan_device.argtypes = [i32, i32, i64, vp, vp, vp]
+    for name in ("se_step", "se_step_bf16g"):
+        fn = getattr(lib, name)
+        fn.restype = i32
+        fn.argtypes = [vp, vp, vp, vp, i32, i32, i32, i64, f32, f32, vp]
+    for name in ("se_ring_step", "se_ring_step_bf16g"):
+        fn = getattr(lib, name)
+        fn.restype = i32
+        fn.argtypes = [vp, vp, vp, vp, i32, i32, f32, f32, vp]
+    lib.se_set_seed.restype = i32
+    lib.se_set_seed.argtypes = [u64]
+    lib.se_get_seed.restype = u64
+    lib.se_get_seed.argtypes = []
+    lib.se_pitch.restype = i64
+    lib.se_pitch.argtypes = [i64]
+    lib.se_step_bytes.restype = i64
+    lib.se_step_bytes.argtypes = [i64, i32, i32, i32]
+    lib.se_set_tuning.restype = i32
+    lib.se_set_tuning.argtypes = [cp, i32]
+    lib.se_get_tuning.restype = i32
+    lib.se_get_tuning.argtypes = [cp]
+    lib.se_strerror.restype = cp
+    lib.se_strerror.argtypes = [i32]
+    lib.se_last_error.restype = cp
+    lib.se_last_error.argtypes = []
+    return lib
+
+
+lib = _load()
+
+
+def _ptr(buf) -> Optional[int]:
+    """Address of a torch tensor / numpy array, an int passed through, or None."""
+    if buf is None:
+        return None
+    if isinstance(buf, int):
+        return buf
+    if hasattr(buf, "data_ptr"):
+        return int(buf.data_ptr())
+    if isinstance(buf, np.ndarray):
+        return int(buf.ctypes.data)
+    raise TypeError(f"cannot take the address of {type(buf)}")
+
+
+def _offsets(layer_offsets: Sequence[int]) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(layer_offsets, dtype=np.int64))
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None      # torch.cuda.Stream
+
+
+def check(code: int) -> None:
+    if code != SE_OK:
+        text = lib.se_strerror(code).decode()
+        if code == SE_ERR_HIP:
+            text += ": " + lib.se_last_error().decode()
+        raise SesgdError(code, text)
+
+
+def se_strerror(code: int) -> str:
+    return lib.se_strerror(code).decode()
+
+
+def se_last_error() -> str:
+    return lib.se_last_error().decode()
+
+
+def se_set_seed(seed: int) -> None:
+    check(lib.se_set_seed(seed & 0xFFFFFFFFFFFFFFFF))
+
+
+def se_get_seed() -> int:
+    return int(lib.se_get_seed())
+
+
+def se_pitch(P: int) -> int:
+    return int(lib.se_pitch(P))
+
+
+def se_step_bytes(pitch: int, n: int, grad_elem_bytes: int = 4, has_momentum: bool = True) -> int:
+    return int(lib.se_step_bytes(pitch, n, grad_elem_bytes, int(has_momentum)))
+
+
+def se_set_tuning(name: str, value: int) -> None:
+    check(lib.se_set_tuning(name.encode(), value))
+
+
+def se_get_tuning(name: str) -> int:
+    return int(lib.se_get_tuning(name.encode()))
+
+
+def se_plan_raw(n, group_size, it, group_of_ptr, members_ptr) -> int:
+    return int(lib.se_plan(n, group_size, it, group_of_ptr, members_ptr))
+
+
+def se_plan(n: int, group_size: int, it: int, want_members: bool = True):
+    """Returns (group_of[n], members[n/group_size, group_size]) as int32 numpy arrays."""
+    group_of = np.full(max(n, 1), -1, np.int32)
+    members = np.full(max(n, 1), -1, np.int32) if want_members else None
+    check(lib.se_plan(n, group_size, it, group_of.ctypes.data,
+                      members.ctypes.data if want_members else None))
+    if want_members:
+        return group_of[:n], members[:n].reshape(n // group_size, group_size)
+    return group_of[:n], None
+
+
+def se_plan_device(n: int, group_size: int, it: int, group_of_dev, members_dev=None, stream=None):
+    check(lib.se_plan_device(n, group_size, it, _ptr(group_of_dev), _ptr(members_dev),
+                             _stream(stream)))
+
+
+def se_step_raw(fn_name, params, grads, momentum, layer_offsets, num_layers, n, group_size, it,
+                lr, mu, stream) -> int:
+    """Unchecked call returning the status code (for error-path tests)."""
+    offs = None if layer_offsets is None else _offsets(layer_offsets)
+    return int(getattr(lib, fn_name)(_ptr(params), _ptr(grads), _ptr(momentum),
+                                     None if offs is None else offs.ctypes.data, num_layers,
+                                     n, group_size, it, lr, mu, _stream(stream)))
+
+
+def se_ring_step_raw(fn_name, params, grads, momentum, layer_offsets, num_layers, n, lr, mu,
+                     stream) -> int:
+    offs = None if layer_offsets is None else _offsets(layer_offsets)
+    return int(getattr(lib, fn_name)(_ptr(params), _ptr(grads), _ptr(momentum),
+                                     None if offs is None else offs.ctypes.data, num_layers,
+                                     n, lr, mu, _stream(stream)))
+
+
+def se_step(params, grads, momentum, layer_offsets, n: int, group_size: int, it: int,
+            lr: float, mu: float, stream=None) -> None:
+    offs = _offsets(layer_offsets)
+    check(lib.se_step(_ptr(params), _ptr(grads), _ptr(momentum), offs.ctypes.data,
+                      len(offs) - 1, n, group_size, it, lr, mu, _stream(stream)))
+
+
+def se_step_bf16g(params, grads_bf16, momentum, layer_offsets, n: int, group_size: int, it: int,
+                  lr: float, mu: float, stream=None) -> None:
+    offs = _offsets(layer_offsets)
+    check(lib.se_step_bf16g(_ptr(params), _ptr(grads_bf16), _ptr(momentum), offs.ctypes.data,
+                            len(offs) - 1, n, group_size, it, lr, mu, _stream(stream)))
+
+
+def se_ring_step(params, grads, momentum, layer_offsets, n: int, lr: float, mu: float,
+                 stream=None) -> None:
+    offs = _offsets(layer_offsets)
+    check(lib.se_ring_step(_ptr(params), _ptr(grads), _ptr(momentum), offs.ctypes.data,
+                           len(offs) - 1, n, lr, mu, _stream(stream)))
+
+
+def se_ring_step_bf16g(params, grads_bf16, momentum, layer_offsets, n: int, lr: float, mu: float,
+                       stream=None) -> None:
+    offs = _offsets(layer_offsets)
+    check(lib.se_ring_step_bf16g(_ptr(params), _ptr(grads_bf16), _ptr(momentum),
+                                 offs.ctypes.data, len(offs) - 1, n, lr, mu, _stream(stream)))

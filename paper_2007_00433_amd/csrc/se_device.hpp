@@ -1,0 +1,117 @@
+// Device-side building blocks: the regrouping generator evaluated by one wavefront, and
+// 128/64/32-bit row accessors addressed as (uniform row base) + (per-lane byte offset).
+#pragma once
+
+#include "se_common.hpp"
+
+namespace se {
+
+// ---------------------------------------------------------------- regrouping (Sec. 3.1)
+// Every worker must derive the same random partition from the shared seed without
+// exchanging messages (Sec. 3.1; Algorithm 1).  Here every wavefront derives it: lane i
+// plays worker i, hashes (seed, iter, n, i) to a 32-bit key, and ranks itself among the n
+// keys (ties by id).  Consecutive blocks of m ranks form the groups.
+
+__device__ __forceinline__ uint32_t mix32(uint32_t z)
+{
+    z ^= z >> 16;
+    z *= 0x6A09E667u;      // frac(sqrt 2) * 2^32
+    z ^= z >> 15;
+    z *= 0xBB67AE85u;      // frac(sqrt 3) * 2^32
+    z ^= z >> 16;
+    return z;
+}
+
+__device__ __forceinline__ uint32_t absorb(uint32_t h, uint32_t w)
+{
+    return mix32((h ^ w) + 0x9E3779B9u);   // 2^32 / golden ratio
+}
+
+__device__ __forceinline__ uint32_t worker_key(uint64_t seed, int64_t iter, int n, int i)
+{
+    uint32_t h = 0x9E3779B9u;
+    h = absorb(h, (uint32_t)seed);
+    h = absorb(h, (uint32_t)(seed >> 32));
+    h = absorb(h, (uint32_t)(uint64_t)iter);
+    h = absorb(h, (uint32_t)((uint64_t)iter >> 32));
+    h = absorb(h, (uint32_t)n);           // everything above is wave-uniform
+    return absorb(h, (uint32_t)i);
+}
+
+// Rank of this lane's worker among workers 0..n-1, n <= 64.  Lanes >= n return garbage.
+__device__ __forceinline__ uint32_t wave_rank(uint64_t seed, int64_t iter, int n, int lane)
+{
+    const uint32_t key = worker_key(seed, iter, n, lane);
+    uint32_t rank = 0;
+    for (int j = 0; j < n; ++j) {
+        const uint32_t kj = (uint32_t)__builtin_amdgcn_readlane((int)key, j);
+        rank += (kj < key || (kj == key && j < lane)) ? 1u : 0u;
+    }
+    return rank;
+}
+
+// Group index of this lane's worker; lanes that are not workers get an impossible group.
+__device__ __forceinline__ uint32_t wave_group_of(uint64_t seed, int64_t iter, int n, int m,
+                                                   int lane)
+{
+    const uint32_t rank = wave_rank(seed, iter, n, lane);
+    return lane < n ? rank / (uint32_t)m : 0xFFFFFFFFu;
+}
+
+// ---------------------------------------------------------------- row accessors
+template <int N> struct Pack { float a[N]; };
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+template <typename T, bool NT> __device__ __forceinline__ T ld(const void *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load((const T *)p);
+    else return *(const T *)p;
+}
+template <typename T, bool NT> __device__ __forceinline__ void st(void *p, T v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, (T *)p);
+    else *(T *)p = v;
+}
+
+// fp32 vector of N columns at byte address p
+template <int N, bool NT> __device__ __forceinline__ Pack<N> load_f32(const char *p)
+{
+    Pack<N> r;
+    if constexpr (N == 4) { f32x4 t = ld<f32x4, NT>(p); r.a[0] = t.x; r.a[1] = t.y; r.a[2] = t.z; r.a[3] = t.w; }
+    else if constexpr (N == 2) { f32x2 t = ld<f32x2, NT>(p); r.a[0] = t.x; r.a[1] = t.y; }
+    else { r.a[0] = ld<float, NT>(p); }
+    return r;
+}
+template <int N, bool NT> __device__ __forceinline__ void store_f32(char *p, const Pack<N> &r)
+{
+    if constexpr (N == 4) { f32x4 t = {r.a[0], r.a[1], r.a[2], r.a[3]}; st<f32x4, NT>(p, t); }
+    else if constexpr (N == 2) { f32x2 t = {r.a[0], r.a[1]}; st<f32x2, NT>(p, t); }
+    else { st<float, NT>(p, r.a[0]); }
+}
+// bf16 vector of N columns at byte address p, widened to fp32 (exact: bits << 16)
+template <int N, bool NT> __device__ __forceinline__ Pack<N> load_bf16(const char *p)
+{
+    Pack<N> r;
+    if constexpr (N == 4) {
+        u16x4 t = ld<u16x4, NT>(p);
+        r.a[0] = __uint_as_float((uint32_t)t.x << 16); r.a[1] = __uint_as_float((uint32_t)t.y << 16);
+        r.a[2] = __uint_as_float((uint32_t)t.z << 16); r.a[3] = __uint_as_float((uint32_t)t.w << 16);
+    } else if constexpr (N == 2) {
+        u16x2 t = ld<u16x2, NT>(p);
+        r.a[0] = __uint_as_float((uint32_t)t.x << 16); r.a[1] = __uint_as_float((uint32_t)t.y << 16);
+    } else {
+        r.a[0] = __uint_as_float((uint32_t)ld<unsigned short, NT>(p) << 16);
+    }
+    return r;
+}
+template <int N, bool BF16, bool NT> __device__ __forceinline__ Pack<N> load_grad(const char *p)
+{
+    if constexpr (BF16) return load_bf16<N, NT>(p);
+    else return load_f32<N, NT>(p);
+}
+
+}  // namespace se

@@ -1,0 +1,129 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2007_00433_amd import binding as se
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # a non-NULL, 16-byte aligned address that is never dereferenced:
+                        # every call below fails validation before any HIP call
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "sesgd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(se_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = header_symbols()
+    assert "se_plan" in names and "se_step" in names and "se_ring_step" in names
+    lib = ctypes.CDLL(se.LIB_PATH)
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(se.EXPORTS) == names
+    for name in names:                      # the Python binding carries the same names
+        assert hasattr(se, name), name
+
+
+def test_error_strings():
+    for code in range(0, -7, -1):
+        assert se.se_strerror(code) and "unknown" not in se.se_strerror(code)
+    assert "unknown" in se.se_strerror(-99)
+
+
+def test_pitch_and_bytes():
+    assert se.se_pitch(0) == 0 and se.se_pitch(1) == 64 and se.se_pitch(64) == 64
+    assert se.se_pitch(5106) == 5120 and se.se_pitch(25557032) == 25557056
+    assert se.se_pitch(-1) == -1
+    assert se.se_step_bytes(25557032, 16, 4, True) == 8178250240      # headline config
+    assert se.se_step_bytes(109482240, 64, 2, True) == 126123540480   # bf16 gradients
+    assert se.se_step_bytes(5106, 4, 4, False) == 245088
+    assert se.se_step_bytes(10, 4, 3, True) == -1
+
+
+def test_seed_and_tuning_state():
+    se.se_set_seed(12345678901234567890)
+    assert se.se_get_seed() == 12345678901234567890
+    se.se_set_seed(0)
+    for name, good, bad in (("grid_blocks_per_cu", 8, -1), ("group_major", 1, 2),
+                            ("nontemporal", 3, 4)):
+        old = se.se_get_tuning(name)
+        se.se_set_tuning(name, good)
+        assert se.se_get_tuning(name) == good
+        with pytest.raises(se.SesgdError):
+            se.se_set_tuning(name, bad)
+        se.se_set_tuning(name, old)
+    with pytest.raises(se.SesgdError):
+        se.se_set_tuning("no_such_knob", 1)
+
+
+OFFS = [0, 100, 228]
+
+
+def step_rc(fn="se_step", params=FAKE, grads=FAKE + (1 << 20), momentum=FAKE + (2 << 20),
+            offs=OFFS, num_layers=None, n=4, m=2, it=0, lr=0.1, mu=0.9):
+    nl = (len(offs) - 1) if num_layers is None and offs is not None else (num_layers or 0)
+    return se.se_step_raw(fn, params, grads, momentum, offs, nl, n, m, it, lr, mu, None)
+
+
+@pytest.mark.parametrize("fn", ["se_step", "se_step_bf16g"])
+def test_step_rejects_bad_arguments_without_a_device(fn):
+    assert step_rc(fn, n=0) == se.SE_ERR_ARG
+    assert step_rc(fn, m=0) == se.SE_ERR_ARG
+    assert step_rc(fn, m=8) == se.SE_ERR_ARG
+    assert step_rc(fn, it=-1) == se.SE_ERR_ARG
+    assert step_rc(fn, num_layers=-1) == se.SE_ERR_ARG
+    assert step_rc(fn, n=6, m=4) == se.SE_ERR_DIVISIBILITY
+    assert step_rc(fn, params=None) == se.SE_ERR_NULL
+    assert step_rc(fn, grads=None) == se.SE_ERR_NULL
+    assert step_rc(fn, offs=None) == se.SE_ERR_NULL
+    assert step_rc(fn, momentum=None, mu=0.9) == se.SE_ERR_NULL
+    assert step_rc(fn, offs=[1, 100, 228]) == se.SE_ERR_LAYOUT
+    assert step_rc(fn, offs=[0, 300, 228]) == se.SE_ERR_LAYOUT
+    assert step_rc(fn, n=128, m=2) == se.SE_ERR_UNSUPPORTED
+    assert step_rc(fn, offs=[0, 1 << 30]) == se.SE_ERR_UNSUPPORTED
+    # overlapping buffers: 4 rows * 228 elements * 4 bytes = 3648 bytes each
+    assert step_rc(fn, grads=FAKE + 3000) == se.SE_ERR_LAYOUT
+    assert step_rc(fn, momentum=FAKE + 3644) == se.SE_ERR_LAYOUT
+    assert step_rc(fn, momentum=FAKE) == se.SE_ERR_LAYOUT
+    # misaligned element pointers
+    assert step_rc(fn, params=FAKE + 2) == se.SE_ERR_LAYOUT
+    assert step_rc(fn, grads=FAKE + (1 << 20) + 1) == se.SE_ERR_LAYOUT
+    # an empty model is a no-op, not an error (nothing is launched)
+    assert step_rc(fn, offs=[0]) == se.SE_OK
+    assert step_rc(fn, offs=[0, 0, 0]) == se.SE_OK
+
+
+@pytest.mark.parametrize("fn", ["se_ring_step", "se_ring_step_bf16g"])
+def test_ring_rejects_bad_arguments_without_a_device(fn):
+    def rc(params=FAKE, grads=FAKE + (1 << 20), momentum=FAKE + (2 << 20), offs=OFFS, n=4, mu=0.9,
+           num_layers=None):
+        nl = (len(offs) - 1) if num_layers is None and offs is not None else (num_layers or 0)
+        return se.se_ring_step_raw(fn, params, grads, momentum, offs, nl, n, 0.1, mu, None)
+    assert rc(n=0) == se.SE_ERR_ARG
+    assert rc(num_layers=-2) == se.SE_ERR_ARG
+    assert rc(params=None) == se.SE_ERR_NULL
+    assert rc(momentum=None) == se.SE_ERR_NULL
+    assert rc(offs=[0, 5, 4]) == se.SE_ERR_LAYOUT
+    assert rc(grads=FAKE + 16) == se.SE_ERR_LAYOUT
+    assert rc(n=65) == se.SE_ERR_UNSUPPORTED
+    assert rc(offs=[0]) == se.SE_OK
+
+
+def test_plan_rejects_bad_arguments_without_a_device():
+    out = np.zeros(64, np.int32)
+    p = out.ctypes.data
+    assert se.se_plan_raw(0, 1, 0, p, p) == se.SE_ERR_ARG
+    assert se.se_plan_raw(4, 0, 0, p, p) == se.SE_ERR_ARG
+    assert se.se_plan_raw(4, 5, 0, p, p) == se.SE_ERR_ARG
+    assert se.se_plan_raw(4, 2, -3, p, p) == se.SE_ERR_ARG
+    assert se.se_plan_raw(6, 4, 0, p, p) == se.SE_ERR_DIVISIBILITY
+    assert se.se_plan_raw(4, 2, 0, None, p) == se.SE_ERR_NULL
+    assert se.se_plan_raw(128, 2, 0, p, p) == se.SE_ERR_UNSUPPORTED
+    assert not out.any()                     # nothing written on error

@@ -1,0 +1,426 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Bar: group indices bit-exact; fp32 results within 1e-6 per-layer
+max-normalised error (util.layer_error).  With the documented fixed evaluation order the
+results are expected to be bit-identical, which is asserted as well.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2007_00433_amd import binding as se
+from paper_2007_00433_amd import workloads as wl
+
+from util import TOL, bit_mismatches, layer_error
+
+pytestmark = pytest.mark.gpu
+
+
+def divisors(n):
+    return [m for m in range(1, n + 1) if n % m == 0]
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(autouse=True)
+def _defaults():
+    se.se_set_seed(0)
+    saved = {k: se.se_get_tuning(k) for k in ("grid_blocks_per_cu", "group_major", "nontemporal")}
+    yield
+    se.se_set_seed(0)
+    for k, v in saved.items():
+        se.se_set_tuning(k, v)
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------ plan
+def test_plan_bit_exact_for_every_n_and_group_size():
+    iters = [0, 1, 2, 3, 7, 255, 2 ** 32 - 1, 2 ** 32, 2 ** 40 + 3]
+    checked = 0
+    for seed in (0, 1, 2 ** 63 + 11):
+        se.se_set_seed(seed)
+        for n in range(1, 65):
+            for m in divisors(n):
+                for it in (iters if n in (4, 16, 64) else iters[:3]):
+                    group_of, members = se.se_plan(n, m, it)
+                    want = oracle.plan(n, m, it, seed=seed)
+                    assert np.array_equal(group_of, want["group_of"]), (seed, n, m, it)
+                    assert np.array_equal(members, want["members"]), (seed, n, m, it)
+                    checked += 1
+    say("plans checked:", checked)
+
+
+def test_plan_golden_vectors(golden_dir):
+    with open(os.path.join(golden_dir, "plan_vectors.json")) as f:
+        cases = json.load(f)["cases"]
+    for c in cases:
+        se.se_set_seed(c["seed"])
+        group_of, members = se.se_plan(c["n"], c["group_size"], c["iter"])
+        assert group_of.tolist() == c["group_of"]
+        assert members.tolist() == c["members"]
+
+
+def test_plan_device_outputs_on_a_side_stream():
+    stream = torch.cuda.Stream()
+    n, m = 64, 8
+    g = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+    mem = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    for it in (0, 5, 2 ** 35):
+        se.se_plan_device(n, m, it, g, mem, stream)
+        stream.synchronize()
+        want = oracle.plan(n, m, it)
+        assert np.array_equal(g.cpu().numpy(), want["group_of"])
+        assert np.array_equal(mem.cpu().numpy().reshape(n // m, m), want["members"])
+    g.fill_(-1)
+    torch.cuda.synchronize()
+    se.se_plan_device(n, m, 3, g, None, stream)       # members optional
+    stream.synchronize()
+    assert np.array_equal(g.cpu().numpy(), oracle.plan(n, m, 3)["group_of"])
+
+
+def test_plan_without_members():
+    group_of, members = se.se_plan(16, 4, 9, want_members=False)
+    assert members is None
+    assert np.array_equal(group_of, oracle.plan(16, 4, 9)["group_of"])
+
+
+# ------------------------------------------------------------------------ step helpers
+class Case:
+    """Device buffers with an optional element shift of the base address (to reach the
+    narrower access paths) and a host mirror for the oracle."""
+
+    def __init__(self, n, ncols, pitch=None, use_v=True, dtype="f32", shift=0, seed=0,
+                 param_std=0.05, v_std=0.0, distinct_rows=False):
+        self.n, self.ncols, self.dtype = n, ncols, dtype
+        self.pitch = ncols if pitch is None else pitch
+        self.seed = seed
+        self.hx = wl.host_params(n, ncols, param_std, seed, self.pitch)
+        if distinct_rows:
+            self.hx[:, :ncols] += wl.host_grads(n, ncols, 0.01, seed, 10 ** 6)[:, :ncols]
+        self.hv = None
+        if use_v:
+            self.hv = np.zeros_like(self.hx)
+            if v_std:
+                self.hv[:, :ncols] = wl.host_grads(n, ncols, v_std, seed, 10 ** 6 + 1)[:, :ncols]
+        self.shift = shift
+        self.dx = self._dev(self.hx, torch.float32)
+        self.dv = self._dev(self.hv, torch.float32) if use_v else None
+        self.dg = None
+
+    def _dev(self, host, tdtype):
+        flat = torch.empty(host.size + 8, dtype=tdtype, device="cuda")
+        view = flat[self.shift:self.shift + host.size]
+        view.copy_(torch.from_numpy(host.reshape(-1).view(np.int16 if host.dtype == np.uint16 else host.dtype)))
+        return view
+
+    def grads(self, it, std):
+        hg = wl.host_grads(self.n, self.ncols, std, self.seed, it, self.dtype, self.pitch)
+        self.dg = self._dev(hg, torch.int16 if self.dtype == "bf16" else torch.float32)
+        return hg
+
+    def offsets(self, sizes=None):
+        offs = [0]
+        for s in (sizes or [self.ncols]):
+            offs.append(offs[-1] + s)
+        assert offs[-1] == self.ncols
+        if self.pitch != self.ncols:
+            offs.append(self.pitch)
+        return offs
+
+    def check(self, what=""):
+        torch.cuda.synchronize()
+        gx = self.dx.cpu().numpy().reshape(self.n, self.pitch)
+        offs = self.offsets()
+        err = layer_error(gx, self.hx, offs)
+        bad = bit_mismatches(gx, self.hx)
+        assert err <= TOL, (what, err)
+        assert bad == 0, (what, "params bit mismatches", bad, err)
+        if self.dv is not None:
+            gv = self.dv.cpu().numpy().reshape(self.n, self.pitch)
+            assert layer_error(gv, self.hv, offs) <= TOL, what
+            assert bit_mismatches(gv, self.hv) == 0, (what, "momentum bit mismatches")
+        return err
+
+
+def run_sesgd(case, m, iters, lr, mu, grad_std, sizes=None, stream=None, first_iter=0):
+    fn = se.se_step_bf16g if case.dtype == "bf16" else se.se_step
+    offs = case.offsets(sizes)
+    for t in range(first_iter, first_iter + iters):
+        hg = case.grads(t, grad_std)
+        fn(case.dx, case.dg, case.dv, offs, case.n, m, t, lr, mu, stream)
+        torch.cuda.synchronize()
+        oracle.step(case.hx, hg, case.hv, m, t, lr, mu, seed=se.se_get_seed())
+
+
+def run_ring(case, iters, lr, mu, grad_std, stream=None):
+    fn = se.se_ring_step_bf16g if case.dtype == "bf16" else se.se_ring_step
+    offs = case.offsets()
+    for t in range(iters):
+        hg = case.grads(t, grad_std)
+        fn(case.dx, case.dg, case.dv, offs, case.n, lr, mu, stream)
+        torch.cuda.synchronize()
+        oracle.ring_step(case.hx, hg, case.hv, lr, mu)
+
+
+# ------------------------------------------------------------------------ step parity
+@pytest.mark.parametrize("use_v", [False, True])
+def test_config_tiny(use_v):
+    """BASELINE config 1: n=4, m=2, tensors [1000, 4096, 10], mu=0, 5 iterations; run both
+    without a momentum buffer and with a zero buffer."""
+    w = wl.WORKLOADS["tiny"]
+    case = Case(w.n, w.P, use_v=use_v)
+    run_sesgd(case, w.group_size, w.iters, w.lr, w.mu, w.grad_std, sizes=list(w.sizes))
+    case.check("tiny")
+
+
+def test_config_resnet20():
+    """BASELINE config 2: n=16, m=4, ResNet-20-shaped (P = 269722, rows only 8-byte aligned),
+    100 iterations with momentum."""
+    w = wl.WORKLOADS["resnet20"]
+    assert w.P == 269722
+    case = Case(w.n, w.P)
+    run_sesgd(case, w.group_size, w.iters, w.lr, w.mu, w.grad_std, sizes=list(w.sizes))
+    case.check("resnet20")
+
+
+def test_config_resnet20_padded_pitch():
+    w = wl.WORKLOADS["resnet20"]
+    pitch = se.se_pitch(w.P)
+    case = Case(w.n, w.P, pitch=pitch)
+    run_sesgd(case, w.group_size, 10, w.lr, w.mu, w.grad_std, sizes=list(w.sizes))
+    case.check("resnet20 padded")
+    # padding columns stay zero
+    gx = case.dx.cpu().numpy().reshape(w.n, pitch)
+    assert not gx[:, w.P:].any()
+
+
+@pytest.mark.parametrize("ncols", [1, 2, 3, 4, 5, 7, 8, 255, 256, 257, 1021, 1024, 1028, 2050, 4099])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ragged_sizes_and_access_widths(ncols, dtype):
+    """Sizes around the tile (256 lanes x 4/2/1 columns) with every pitch alignment class."""
+    case = Case(8, ncols, dtype=dtype, distinct_rows=True, v_std=0.01)
+    run_sesgd(case, 4, 3, 0.1, 0.9, 1e-2)
+    case.check(f"ragged {ncols} {dtype}")
+
+
+@pytest.mark.parametrize("shift", [1, 2, 4])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_misaligned_base_addresses(shift, dtype):
+    """Buffers that start 4, 8 or 16 bytes into an allocation: narrower accesses are chosen."""
+    case = Case(8, 1536, dtype=dtype, shift=shift, distinct_rows=True, v_std=0.01)
+    run_sesgd(case, 2, 3, 0.1, 0.9, 1e-2)
+    case.check(f"shift {shift} {dtype}")
+    case = Case(8, 1536, dtype=dtype, shift=shift)
+    run_ring(case, 2, 0.1, 0.9, 1e-2)
+    case.check(f"ring shift {shift} {dtype}")
+
+
+@pytest.mark.parametrize("n,ms", [(64, [1, 2, 4, 8, 16, 32, 64]), (12, [1, 2, 3, 4, 6, 12]),
+                                  (63, [7, 9, 21]), (5, [1, 5]), (1, [1]), (30, [15, 10])])
+def test_group_sizes(n, ms):
+    for m in ms:
+        for use_v in (True, False):
+            case = Case(n, 1300, use_v=use_v, distinct_rows=True, v_std=0.01 if use_v else 0.0)
+            run_sesgd(case, m, 3, 0.1, 0.9 if use_v else 0.0, 1e-2)
+            case.check(f"n={n} m={m} v={use_v}")
+
+
+def test_large_iteration_numbers_and_seed():
+    se.se_set_seed(0xDEADBEEFCAFEF00D)
+    case = Case(16, 2000, distinct_rows=True)
+    run_sesgd(case, 4, 3, 0.1, 0.9, 1e-2, first_iter=2 ** 40 + 1)
+    case.check("big iter")
+
+
+def test_bert_shaped_bf16_small():
+    """Config 5's arithmetic at a reduced width: n=64, m=8 and m=64, bf16 gradients."""
+    for m in (8, 64):
+        case = Case(64, 3 * 768 + 2, dtype="bf16")
+        run_sesgd(case, m, 4, 1e-4, 0.9, 1e-3)
+        case.check(f"bert small m={m}")
+
+
+@pytest.mark.parametrize("n", [1, 2, 7, 8, 9, 16, 33, 64])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ring_parity(n, dtype):
+    for use_v in (True, False):
+        case = Case(n, 2051 if n % 2 else 2052, use_v=use_v, dtype=dtype, v_std=0.01 if use_v else 0.0)
+        run_ring(case, 3, 0.1, 0.9 if use_v else 0.0, 1e-2)
+        case.check(f"ring n={n} {dtype} v={use_v}")
+
+
+def test_ring_config_resnet20():
+    w = wl.WORKLOADS["resnet20"]
+    case = Case(w.n, w.P)
+    run_ring(case, 20, w.lr, w.mu, w.grad_std)
+    case.check("ring resnet20")
+
+
+def test_full_group_equals_ring_on_the_gpu():
+    """group_size = n from identical starts reduces to the full Ring-SGD average, up to
+    fp32 rounding (momentum buffers differ by design: per worker vs shared)."""
+    n, P, T = 16, 40000, 20
+    a, b = Case(n, P), Case(n, P)
+    offs = a.offsets()
+    for t in range(T):
+        a.grads(t, 1e-2)
+        b.dg = a.dg
+        se.se_step(a.dx, a.dg, a.dv, offs, n, n, t, 0.1, 0.9)
+        se.se_ring_step(b.dx, b.dg, b.dv, offs, n, 0.1, 0.9)
+    torch.cuda.synchronize()
+    xa = a.dx.cpu().numpy().reshape(n, P)
+    xb = b.dx.cpu().numpy().reshape(n, P)
+    assert layer_error(xa, xb, offs) <= TOL
+
+
+def test_special_values_propagate():
+    """Denormals are kept (no flush to zero); NaN and Inf propagate inside their group only."""
+    n, m, P = 4, 2, 512
+    case = Case(n, P, distinct_rows=True)
+    case.hx[:, 0] = np.float32(1e-40)
+    case.hx[:, 1] = np.float32(3e-39)
+    case.hx[0, 2] = np.inf
+    case.hx[1, 3] = np.nan
+    case.dx.copy_(torch.from_numpy(case.hx.reshape(-1)))
+    hg = case.grads(0, 1e-2)
+    hg[:, :2] = np.float32(1e-41)
+    case.dg.copy_(torch.from_numpy(hg.reshape(-1)))
+    se.se_step(case.dx, case.dg, case.dv, case.offsets(), n, m, 0, 0.5, 0.9)
+    oracle.step(case.hx, hg, case.hv, m, 0, 0.5, 0.9)
+    torch.cuda.synchronize()
+    gx = case.dx.cpu().numpy().reshape(n, P)
+    assert bit_mismatches(gx[:, :2], case.hx[:, :2]) == 0
+    assert (gx[:, 0] != 0).all() and (np.abs(gx[:, 0]) < 1.2e-38).all()     # still denormal
+    assert np.array_equal(np.isnan(gx), np.isnan(case.hx))
+    assert np.array_equal(np.isinf(gx), np.isinf(case.hx))
+    assert np.isnan(gx[:, 3]).sum() == m and np.isinf(gx[:, 2]).sum() == m
+    finite = np.isfinite(case.hx)
+    assert np.array_equal(gx[finite], case.hx[finite])
+
+
+def test_results_do_not_depend_on_launch_knobs_or_stream():
+    ref = None
+    stream = torch.cuda.Stream()
+    for bpc, gm, nt, st in [(0, 0, 0, None), (4, 0, 0, None), (1, 1, 0, None), (0, 1, 3, None),
+                            (16, 0, 1, stream), (2, 1, 2, stream)]:
+        se.se_set_tuning("grid_blocks_per_cu", bpc)
+        se.se_set_tuning("group_major", gm)
+        se.se_set_tuning("nontemporal", nt)
+        case = Case(16, 70001 * 4, distinct_rows=True, v_std=0.01)
+        torch.cuda.synchronize()
+        offs = case.offsets()
+        for t in range(3):
+            case.grads(t, 1e-2)
+            torch.cuda.synchronize()
+            se.se_step(case.dx, case.dg, case.dv, offs, 16, 4, t, 0.1, 0.9, st)
+            se.se_ring_step(case.dx, case.dg, case.dv, offs, 16, 0.1, 0.9, st)
+            (st or torch.cuda.current_stream()).synchronize()
+        got = (case.dx.cpu().numpy().copy(), case.dv.cpu().numpy().copy())
+        if ref is None:
+            ref = got
+            # and the reference itself matches the oracle
+            for t in range(3):
+                hg = wl.host_grads(16, case.ncols, 1e-2, 0, t)
+                oracle.step(case.hx, hg, case.hv, 4, t, 0.1, 0.9)
+                oracle.ring_step(case.hx, hg, case.hv, 0.1, 0.9)
+            case.check("knobs reference")
+        else:
+            assert bit_mismatches(got[0], ref[0]) == 0 and bit_mismatches(got[1], ref[1]) == 0
+
+
+def test_resume_from_any_iteration():
+    """The plan is a pure function of (seed, n, iter): 0..7 in one go equals 0..3 then 4..7."""
+    a, b = Case(16, 5000), Case(16, 5000)
+    run_sesgd(a, 4, 8, 0.1, 0.9, 1e-2)
+    run_sesgd(b, 4, 4, 0.1, 0.9, 1e-2)
+    run_sesgd(b, 4, 4, 0.1, 0.9, 1e-2, first_iter=4)
+    torch.cuda.synchronize()
+    assert torch.equal(a.dx, b.dx) and torch.equal(a.dv, b.dv)
+
+
+def test_error_codes_on_the_device_box():
+    x = torch.zeros(4 * 256, device="cuda")
+    g = torch.zeros(4 * 256, device="cuda")
+    assert se.se_step_raw("se_step", x, g, None, [0, 256], 1, 4, 3, 0, 0.1, 0.0, None) == se.SE_ERR_DIVISIBILITY
+    assert se.se_step_raw("se_step", x, g, None, [0, 256], 1, 4, 2, 0, 0.1, 0.5, None) == se.SE_ERR_NULL
+    assert se.se_step_raw("se_step", x, x, None, [0, 256], 1, 4, 2, 0, 0.1, 0.0, None) == se.SE_ERR_LAYOUT
+    torch.cuda.synchronize()
+    assert not x.any()
+
+
+# ------------------------------------------------------------------------ full size, sampled
+def _full_size_sampled(name, iters, ring=False):
+    """The benchmark's launch configuration at the workload's full size.  Inputs are drawn on
+    the device by torch (seeded); the oracle replays the sampled columns exactly, because
+    columns are independent.  Also checks the any-size properties: members of a group end
+    bit-identical, and untouched padding stays zero."""
+    w = wl.WORKLOADS[name]
+    n, m, P = w.n, w.group_size, w.P
+    pitch = se.se_pitch(P)
+    offs = w.layer_offsets(pitch)
+    bf16 = w.grad_dtype == "bf16"
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234)
+    say(f"{name}: n={n} m={m} P={P} pitch={pitch} resident={(n * pitch * (8 + w.grad_bytes)) / 2**30:.1f} GiB")
+    x = torch.zeros(n, pitch, device="cuda")
+    row = torch.randn(P, device="cuda", generator=gen) * w.param_std
+    x[:, :P] = row
+    del row
+    v = torch.zeros(n, pitch, device="cuda")
+    g = torch.zeros(n, pitch, device="cuda", dtype=torch.bfloat16 if bf16 else torch.float32)
+    cols = torch.from_numpy(wl.sample_columns(pitch, 20000, seed=1)).cuda()
+    hx = x[:, cols].cpu().numpy().copy()
+    hv = v[:, cols].cpu().numpy().copy()
+    soffs = [0, hx.shape[1]]
+    for t in range(iters):
+        for i in range(n):                       # row by row keeps the temporaries small
+            g[i, :P] = (torch.randn(P, device="cuda", generator=gen) * w.grad_std).to(g.dtype)
+        hg = g[:, cols]
+        hg = (hg.view(torch.int16).cpu().numpy().view(np.uint16) if bf16 else hg.cpu().numpy()).copy()
+        torch.cuda.synchronize()
+        if ring:
+            (se.se_ring_step_bf16g if bf16 else se.se_ring_step)(x, g, v, offs, n, w.lr, w.mu)
+            oracle.ring_step(hx, hg, hv, w.lr, w.mu)
+        else:
+            (se.se_step_bf16g if bf16 else se.se_step)(x, g, v, offs, n, m, t, w.lr, w.mu)
+            oracle.step(hx, hg, hv, m, t, w.lr, w.mu)
+        torch.cuda.synchronize()
+        say(f"  iter {t} done")
+    gx = x[:, cols].cpu().numpy()
+    gv = v[:, cols].cpu().numpy()
+    assert layer_error(gx, hx, soffs) <= TOL and layer_error(gv, hv, soffs) <= TOL
+    assert bit_mismatches(gx, hx) == 0 and bit_mismatches(gv, hv) == 0
+    if not ring:
+        members = oracle.plan(n, m, iters - 1)["members"]
+        for rowm in members[:2]:
+            for wkr in rowm[1:]:
+                assert torch.equal(x[int(rowm[0])], x[int(wkr)])
+    assert not x[:, P:].any() and not v[:, P:].any()
+    del x, v, g
+    torch.cuda.empty_cache()
+
+
+def test_full_size_resnet50_sampled():
+    _full_size_sampled("resnet50", 4)
+
+
+def test_full_size_resnet50_ring_sampled():
+    _full_size_sampled("resnet50", 2, ring=True)
+
+
+def test_full_size_vgg16_sampled():
+    _full_size_sampled("vgg16", 2)
+
+
+def test_full_size_bert_base_sampled():
+    _full_size_sampled("bert_base", 2)
+
+
+def test_full_size_bert_base_full_group_sampled():
+    _full_size_sampled("bert_base_full", 2)
