@@ -9,6 +9,9 @@ import os
 from typing import Optional, Sequence
 
 import numpy as np
+import torch  # noqa: F401  -- must come first: torch ships its own HIP runtime, and two
+#                              HIP runtimes in one process cannot both open the GPU.  Loaded
+#                              after torch, libsesgd.so binds to torch's runtime by soname.
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libsesgd.so")
@@ -38,6 +41,13 @@ def _load() -> ctypes.CDLL:
         raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2007_00433_amd.build` "
                           "(there is no CPU fallback)")
     lib = ctypes.CDLL(LIB_PATH)
+    runtimes = set()
+    with open("/proc/self/maps") as maps:
+        for line in maps:
+            if "libamdhip64" in line:
+                runtimes.add(line.split()[-1])
+    if len(runtimes) > 1:
+        raise ImportError(f"two HIP runtimes are loaded in this process: {sorted(runtimes)}")
     i32, i64, u64 = ctypes.c_int, ctypes.c_int64, ctypes.c_uint64
     vp, f32, cp = ctypes.c_void_p, ctypes.c_float, ctypes.c_char_p
     lib.se_plan.restype = i32
