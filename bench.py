@@ -33,6 +33,7 @@ def parse():
     ap.add_argument("--no-pad", action="store_true", help="use pitch = P instead of se_pitch(P)")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--skip-ring", action="store_true")
+    ap.add_argument("--skip-copy", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=3.0, help="target CPU time per oracle leg")
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE")
     return ap.parse_args()
@@ -152,6 +153,15 @@ def main():
     bytes_per_launch = se.se_step_bytes(pitch, n, w.grad_bytes, True)
     achieved = bytes_per_launch / per_launch / 1e9
 
+    # HBM bytes per launch measured offline with rocprofv3 --pmc (see profiles/*.md)
+    traffic = None
+    prof = os.path.join(ROOT, "profiles", f"se_step_{args.workload}_n{n}_m{m}.json")
+    if os.path.exists(prof):
+        with open(prof) as f:
+            pj = json.load(f)
+        if pj.get("pitch") == pitch:
+            traffic = pj["kernels"].get("se_step_kernel", {}).get("traffic_bytes")
+
     out = {
         "metric": "SESGD steps/sec and achieved HBM GB/s (% of peak), n=16 ResNet-50-shaped"
                   if args.workload == "resnet50" else f"SESGD steps/sec, {args.workload}",
@@ -170,9 +180,17 @@ def main():
                               ("grid_blocks_per_cu", "group_major", "nontemporal")}},
         "roofline": {"bound": "hbm", "kernel": "se_step_kernel", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": None, "bytes_per_launch": bytes_per_launch,
+                     "traffic": traffic, "bytes_per_launch": bytes_per_launch,
                      "avg_launch_ms": round(per_launch * 1e3, 5)},
     }
+    # practical ceiling: a plain streaming copy over buffers of the same size
+    nb = pool[0].numel() * pool[0].element_size()
+    if not args.skip_copy and len(pool) > 1:
+        a_buf, b_buf = pool[0].reshape(-1), pool[1].reshape(-1)
+        _, cper = timed_steps(lambda t, stream: se.se_calib_copy(b_buf, a_buf, nb, stream),
+                              max(10, args.steps // 2), 3, torch)
+        out["copy_ceiling"] = {"achieved_gbs": round(2 * nb / cper / 1e9, 1), "bytes_per_launch": 2 * nb,
+                               "kernel": "se_calib_copy_kernel"}
     if not args.skip_ring:
         rwall, rper = timed_steps(launch_ring, args.steps, args.warmup, torch)
         out["ring_baseline"] = {"value": round(args.steps / rwall, 3), "unit": "steps/s",

@@ -117,10 +117,22 @@ int64_t se_pitch(int64_t P);
  * the numerator of the achieved-bandwidth figure: n*pitch*(8 + grad bytes + 8 if momentum). */
 int64_t se_step_bytes(int64_t pitch, int n, int grad_elem_bytes, int has_momentum);
 
+/* Measurement helper, not part of the method: copies nbytes (a multiple of 16, below 2^37)
+ * between two non-overlapping, 16-byte aligned DEVICE buffers with a plain streaming kernel
+ * on `stream`.  Reads nbytes and writes nbytes: the reference reading for the profiler's HBM
+ * byte counters and a practical bandwidth ceiling next to se_step's figure. */
+int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
+
 /* Launch-shape knobs for measurement sweeps; results never depend on them.
- *   "grid_blocks_per_cu"  blocks per compute unit of the grid-stride launch (0 = one block per tile)
- *   "group_major"         1: all tiles of group 0 first; 0: the groups of one tile side by side
- *   "nontemporal"         bit 0: non-temporal loads, bit 1: non-temporal stores
+ *   "block_threads"       threads per workgroup: 64 (default), 128 or 256
+ *   "max_blocks_per_cu"   cap on resident workgroups per compute unit, enforced by requesting
+ *                         160 KiB / cap of (unused) LDS per workgroup; 0 = no cap (default 8)
+ *   "tiles_per_block"     consecutive tiles one workgroup of se_step walks through (default 1)
+ *   "group_major"         se_step block order. 1 (default): all tiles of group 0, then group 1,
+ *                         ...; 0: the groups of one tile side by side
+ *   "nontemporal"         bit 0: non-temporal loads, bit 1: non-temporal stores (default 3)
+ *   "grid_blocks_per_cu"  se_ring_step only: grid-stride launch with this many workgroups per
+ *                         compute unit; 0 (default) = one workgroup per tile
  * Returns SE_ERR_ARG for an unknown name or a value out of range. */
 int se_set_tuning(const char *name, int value);
 int se_get_tuning(const char *name);

@@ -27,7 +27,11 @@ SE_MAX_WORKERS = 64
 
 EXPORTS = ("se_plan", "se_plan_device", "se_step", "se_step_bf16g", "se_ring_step",
            "se_ring_step_bf16g", "se_set_seed", "se_get_seed", "se_pitch", "se_step_bytes",
-           "se_set_tuning", "se_get_tuning", "se_strerror", "se_last_error")
+           "se_set_tuning", "se_get_tuning", "se_strerror", "se_last_error", "se_calib_copy")
+
+
+TUNING_KNOBS = ("block_threads", "max_blocks_per_cu", "tiles_per_block", "group_major",
+                "nontemporal", "grid_blocks_per_cu")
 
 
 class SesgdError(RuntimeError):
@@ -74,6 +78,8 @@ def _load() -> ctypes.CDLL:
     lib.se_set_tuning.argtypes = [cp, i32]
     lib.se_get_tuning.restype = i32
     lib.se_get_tuning.argtypes = [cp]
+    lib.se_calib_copy.restype = i32
+    lib.se_calib_copy.argtypes = [vp, vp, i64, vp]
     lib.se_strerror.restype = cp
     lib.se_strerror.argtypes = [i32]
     lib.se_last_error.restype = cp
@@ -147,6 +153,10 @@ def se_set_tuning(name: str, value: int) -> None:
 
 def se_get_tuning(name: str) -> int:
     return int(lib.se_get_tuning(name.encode()))
+
+
+def se_calib_copy(dst, src, nbytes: int, stream=None) -> None:
+    check(lib.se_calib_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
 
 
 def se_plan_raw(n, group_size, it, group_of_ptr, members_ptr) -> int:

@@ -14,9 +14,12 @@
 namespace {
 
 std::atomic<uint64_t> g_seed{0};
-std::atomic<int> g_blocks_per_cu{0};
-std::atomic<int> g_group_major{0};
-std::atomic<int> g_nontemporal{0};
+std::atomic<int> g_blocks_per_cu{0};     // ring kernel: grid-stride blocks per CU (0 = one per tile)
+std::atomic<int> g_group_major{1};
+std::atomic<int> g_nontemporal{3};
+std::atomic<int> g_block_threads{64};
+std::atomic<int> g_tiles_per_block{1};
+std::atomic<int> g_max_blocks_per_cu{8};  // step kernel: resident workgroups per CU (0 = no cap)
 
 thread_local char t_last_error[256] = "";
 
@@ -112,15 +115,20 @@ int step_impl(float *params, const void *grads, float *momentum, const int64_t *
     a.x = params; a.g = grads; a.v = momentum;
     a.seed = g_seed.load(); a.iter = iter;
     a.pitch_bytes = (uint64_t)lay.pitch * 4u;
+    se::LaunchShape s;
+    s.vec = lay.vec; s.bf16 = grad_bytes == 2; s.nontemporal = g_nontemporal.load();
+    s.block = g_block_threads.load();
+    const int cap = g_max_blocks_per_cu.load();
+    s.lds_bytes = cap > 0 ? (se::kLdsPerCu / (uint32_t)cap) & ~1023u : 0u;
+
     a.nvec = (uint32_t)(lay.pitch / lay.vec);
-    a.tiles = (a.nvec + se::kBlock - 1) / se::kBlock;
+    a.tiles = (a.nvec + (uint32_t)s.block - 1) / (uint32_t)s.block;
+    a.tiles_per_block = (uint32_t)g_tiles_per_block.load();
+    a.chunks = (a.tiles + a.tiles_per_block - 1) / a.tiles_per_block;
     a.n = n; a.m = group_size; a.k = n / group_size;
     a.neg_lr = -lr; a.mu = mu; a.inv_m = 1.0f / (float)group_size;
     a.group_major = g_group_major.load();
-
-    se::LaunchShape s;
-    s.vec = lay.vec; s.bf16 = grad_bytes == 2; s.nontemporal = g_nontemporal.load();
-    s.grid = grid_for((uint64_t)a.tiles * (uint64_t)a.k);
+    s.grid = a.chunks * (uint32_t)a.k;        // < 2^30 / 64 * 64 workgroups
     const hipError_t e = se::launch_step(a, s, (hipStream_t)stream);
     return e == hipSuccess ? SE_OK : hip_fail("se_step launch", e);
 }
@@ -137,13 +145,15 @@ int ring_impl(float *params, const void *grads, float *momentum, const int64_t *
     se::RingArgs a;
     a.x = params; a.g = grads; a.v = momentum;
     a.pitch_bytes = (uint64_t)lay.pitch * 4u;
-    a.nvec = (uint32_t)(lay.pitch / lay.vec);
-    a.tiles = (a.nvec + se::kBlock - 1) / se::kBlock;
-    a.n = n;
-    a.neg_lr = -lr; a.mu = mu; a.inv_n = 1.0f / (float)n;
-
     se::LaunchShape s;
     s.vec = lay.vec; s.bf16 = grad_bytes == 2; s.nontemporal = g_nontemporal.load();
+    s.block = g_block_threads.load();
+    const int cap = g_max_blocks_per_cu.load();
+    s.lds_bytes = cap > 0 ? (se::kLdsPerCu / (uint32_t)cap) & ~1023u : 0u;
+    a.nvec = (uint32_t)(lay.pitch / lay.vec);
+    a.tiles = (a.nvec + (uint32_t)s.block - 1) / (uint32_t)s.block;
+    a.n = n;
+    a.neg_lr = -lr; a.mu = mu; a.inv_n = 1.0f / (float)n;
     s.grid = grid_for(a.tiles);
     const hipError_t e = se::launch_ring(a, s, (hipStream_t)stream);
     return e == hipSuccess ? SE_OK : hip_fail("se_ring_step launch", e);
@@ -217,6 +227,18 @@ int se_ring_step_bf16g(float *params, const uint16_t *grads_bf16, float *momentu
     return ring_impl(params, grads_bf16, momentum, layer_offsets, num_layers, n, lr, mu, stream, 2);
 }
 
+int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream)
+{
+    if (nbytes < 0) return SE_ERR_ARG;
+    if (!dst || !src) return SE_ERR_NULL;
+    if ((uintptr_t)dst % 16 || (uintptr_t)src % 16 || nbytes % 16 || nbytes >= ((int64_t)1 << 37) ||
+        overlaps(dst, (uint64_t)nbytes, src, (uint64_t)nbytes))
+        return SE_ERR_LAYOUT;
+    if (nbytes == 0) return SE_OK;
+    const hipError_t e = se::launch_calib_copy(dst, src, (uint64_t)nbytes, (hipStream_t)stream);
+    return e == hipSuccess ? SE_OK : hip_fail("se_calib_copy launch", e);
+}
+
 int se_set_seed(uint64_t seed) { g_seed.store(seed); return SE_OK; }
 uint64_t se_get_seed(void) { return g_seed.load(); }
 
@@ -243,6 +265,18 @@ int se_set_tuning(const char *name, int value)
         if (value < 0 || value > 1) return SE_ERR_ARG;
         g_group_major.store(value); return SE_OK;
     }
+    if (!std::strcmp(name, "block_threads")) {
+        if (value != 64 && value != 128 && value != 256) return SE_ERR_ARG;
+        g_block_threads.store(value); return SE_OK;
+    }
+    if (!std::strcmp(name, "tiles_per_block")) {
+        if (value < 1 || value > 65536) return SE_ERR_ARG;
+        g_tiles_per_block.store(value); return SE_OK;
+    }
+    if (!std::strcmp(name, "max_blocks_per_cu")) {
+        if (value < 0 || value > 32) return SE_ERR_ARG;
+        g_max_blocks_per_cu.store(value); return SE_OK;
+    }
     if (!std::strcmp(name, "nontemporal")) {
         if (value < 0 || value > 3) return SE_ERR_ARG;
         g_nontemporal.store(value); return SE_OK;
@@ -256,6 +290,9 @@ int se_get_tuning(const char *name)
     if (!std::strcmp(name, "grid_blocks_per_cu")) return g_blocks_per_cu.load();
     if (!std::strcmp(name, "group_major")) return g_group_major.load();
     if (!std::strcmp(name, "nontemporal")) return g_nontemporal.load();
+    if (!std::strcmp(name, "block_threads")) return g_block_threads.load();
+    if (!std::strcmp(name, "tiles_per_block")) return g_tiles_per_block.load();
+    if (!std::strcmp(name, "max_blocks_per_cu")) return g_max_blocks_per_cu.load();
     return SE_ERR_ARG;
 }
 

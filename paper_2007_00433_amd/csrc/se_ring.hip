@@ -4,18 +4,20 @@
 // n gradient rows in ascending worker id, scales by 1/n, then updates all n rows.
 #include "se_device.hpp"
 
+#include <atomic>
+
 namespace se {
 
-template <int VEC, bool BF16, bool HAS_V, bool NTL, bool NTS>
-__global__ __launch_bounds__(kBlock) void se_ring_kernel(const RingArgs p)
+template <int VEC, bool BF16, bool HAS_V, bool NTL, bool NTS, int BS>
+__global__ __launch_bounds__(BS) void se_ring_kernel(const RingArgs p)
 {
     constexpr int GB = 8;     // gradient rows in flight per lane
     constexpr int UB = 4;     // parameter/momentum rows in flight per lane
     const uint64_t gpitch_bytes = BF16 ? p.pitch_bytes / 2 : p.pitch_bytes;
 
     for (uint32_t tile = blockIdx.x; tile < p.tiles; tile += gridDim.x) {
-        const uint32_t c = tile * (uint32_t)kBlock + threadIdx.x;
-        if (c >= p.nvec) continue;
+        const uint32_t c = tile * (uint32_t)BS + threadIdx.x;
+        if (c >= p.nvec) break;
         const uint32_t off = c * (uint32_t)(VEC * 4);
         const uint32_t goff = BF16 ? off / 2 : off;
 
@@ -82,17 +84,42 @@ __global__ __launch_bounds__(kBlock) void se_ring_kernel(const RingArgs p)
     }
 }
 
+template <int VEC, bool BF16, bool HAS_V, int BS>
+static hipError_t launch_bs(const RingArgs &a, const LaunchShape &s, hipStream_t stream)
+{
+    dim3 grid(s.grid), block(BS);
+    const size_t lds = s.lds_bytes;
+#define SE_LAUNCH(NTL, NTS)                                                                     \
+    do {                                                                                        \
+        auto kern = se_ring_kernel<VEC, BF16, HAS_V, NTL, NTS, BS>;                             \
+        static std::atomic<bool> raised{false};                                                 \
+        if (lds > 0 && !raised.load()) {                                                        \
+            hipError_t e = hipFuncSetAttribute((const void *)kern,                              \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,      \
+                                               (int)kLdsPerCu);                                 \
+            if (e != hipSuccess) return e;                                                      \
+            raised.store(true);                                                                 \
+        }                                                                                       \
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, a);                                  \
+    } while (0)
+    switch (s.nontemporal & 3) {
+    case 0: SE_LAUNCH(false, false); break;
+    case 1: SE_LAUNCH(true, false); break;
+    case 2: SE_LAUNCH(false, true); break;
+    default: SE_LAUNCH(true, true); break;
+    }
+#undef SE_LAUNCH
+    return hipGetLastError();
+}
+
 template <int VEC, bool BF16, bool HAS_V>
 static hipError_t launch_nt(const RingArgs &a, const LaunchShape &s, hipStream_t stream)
 {
-    dim3 grid(s.grid), block(kBlock);
-    switch (s.nontemporal & 3) {
-    case 0: hipLaunchKernelGGL((se_ring_kernel<VEC, BF16, HAS_V, false, false>), grid, block, 0, stream, a); break;
-    case 1: hipLaunchKernelGGL((se_ring_kernel<VEC, BF16, HAS_V, true, false>), grid, block, 0, stream, a); break;
-    case 2: hipLaunchKernelGGL((se_ring_kernel<VEC, BF16, HAS_V, false, true>), grid, block, 0, stream, a); break;
-    default: hipLaunchKernelGGL((se_ring_kernel<VEC, BF16, HAS_V, true, true>), grid, block, 0, stream, a); break;
+    switch (s.block) {
+    case 64: return launch_bs<VEC, BF16, HAS_V, 64>(a, s, stream);
+    case 128: return launch_bs<VEC, BF16, HAS_V, 128>(a, s, stream);
+    default: return launch_bs<VEC, BF16, HAS_V, 256>(a, s, stream);
     }
-    return hipGetLastError();
 }
 
 template <int VEC, bool BF16>

@@ -2,7 +2,8 @@
 // Algorithm 1 loop body): regroup, local SGD/momentum step into x-hat, mean of x-hat over
 // the group, write the mean to every member -- one pass over the packed buffer.
 //
-// Work decomposition: a task is (group g, tile of kBlock lane-columns).  A lane owns VEC
+// Work decomposition: a workgroup handles one group g and a run of consecutive tiles of
+// BS lane-columns.  A lane owns VEC
 // consecutive columns of ALL member rows of its group, so x-hat never leaves registers and
 // the group mean needs no cross-lane traffic; a wavefront touches 64*VEC*4 contiguous
 // bytes of each member row per access.  The member list of group g is the bit mask
@@ -11,6 +12,8 @@
 // wave-uniform, so row bases live in scalar registers and every row access is
 // (scalar base) + (one shared 32-bit lane offset).
 #include "se_device.hpp"
+
+#include <atomic>
 
 namespace se {
 
@@ -47,23 +50,26 @@ __device__ __forceinline__ void member_batch(const StepArgs &p, uint64_t &todo, 
     }
 }
 
-template <int VEC, bool BF16, bool HAS_V, bool NTL, bool NTS, int BMAX>
-__global__ __launch_bounds__(kBlock) void se_step_kernel(const StepArgs p)
+template <int VEC, bool BF16, bool HAS_V, bool NTL, bool NTS, int BMAX, int BS>
+__global__ __launch_bounds__(BS) void se_step_kernel(const StepArgs p)
 {
     const int lane = (int)(threadIdx.x & 63u);
     // Regrouping for this iteration, redone by every wavefront (a few hundred integer
-    // instructions, amortised over all tasks of the grid-stride loop).
+    // instructions, amortised over the tiles_per_block tiles the block walks through).
     const uint32_t grp = wave_group_of(p.seed, p.iter, p.n, p.m, lane);
-    const uint32_t ntasks = p.tiles * (uint32_t)p.k;
     const uint64_t gpitch_bytes = BF16 ? p.pitch_bytes / 2 : p.pitch_bytes;
 
-    for (uint32_t task = blockIdx.x; task < ntasks; task += gridDim.x) {
-        uint32_t g, tile;
-        if (p.group_major) { g = task / p.tiles; tile = task - g * p.tiles; }
-        else               { tile = task / (uint32_t)p.k; g = task - tile * (uint32_t)p.k; }
-        const uint64_t members = __ballot(grp == g);       // wave-uniform, m bits set
-        const uint32_t c = tile * (uint32_t)kBlock + threadIdx.x;
-        if (c >= p.nvec) continue;
+    // block -> (group g, run of consecutive tiles)
+    uint32_t g, chunk;
+    if (p.group_major) { g = blockIdx.x / p.chunks; chunk = blockIdx.x - g * p.chunks; }
+    else               { chunk = blockIdx.x / (uint32_t)p.k; g = blockIdx.x - chunk * (uint32_t)p.k; }
+    const uint64_t members = __ballot(grp == g);           // wave-uniform, m bits set
+    const uint32_t tile0 = chunk * p.tiles_per_block;
+    const uint32_t tile1 = min(tile0 + p.tiles_per_block, p.tiles);
+
+    for (uint32_t tile = tile0; tile < tile1; ++tile) {
+        const uint32_t c = tile * (uint32_t)BS + threadIdx.x;
+        if (c >= p.nvec) break;
         const uint32_t off = c * (uint32_t)(VEC * 4);
         const uint32_t goff = BF16 ? off / 2 : off;
 
@@ -106,17 +112,42 @@ __global__ __launch_bounds__(kBlock) void se_step_kernel(const StepArgs p)
     }
 }
 
+template <int VEC, bool BF16, bool HAS_V, int BMAX, int BS>
+static hipError_t launch_bs(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
+{
+    dim3 grid(s.grid), block(BS);
+    const size_t lds = s.lds_bytes;
+#define SE_LAUNCH(NTL, NTS)                                                                     \
+    do {                                                                                        \
+        auto kern = se_step_kernel<VEC, BF16, HAS_V, NTL, NTS, BMAX, BS>;                       \
+        static std::atomic<bool> raised{false};                                                 \
+        if (lds > 0 && !raised.load()) {                                                        \
+            hipError_t e = hipFuncSetAttribute((const void *)kern,                              \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,      \
+                                               (int)kLdsPerCu);                                 \
+            if (e != hipSuccess) return e;                                                      \
+            raised.store(true);                                                                 \
+        }                                                                                       \
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, a);                                  \
+    } while (0)
+    switch (s.nontemporal & 3) {
+    case 0: SE_LAUNCH(false, false); break;
+    case 1: SE_LAUNCH(true, false); break;
+    case 2: SE_LAUNCH(false, true); break;
+    default: SE_LAUNCH(true, true); break;
+    }
+#undef SE_LAUNCH
+    return hipGetLastError();
+}
+
 template <int VEC, bool BF16, bool HAS_V, int BMAX>
 static hipError_t launch_nt(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
-    dim3 grid(s.grid), block(kBlock);
-    switch (s.nontemporal & 3) {
-    case 0: hipLaunchKernelGGL((se_step_kernel<VEC, BF16, HAS_V, false, false, BMAX>), grid, block, 0, stream, a); break;
-    case 1: hipLaunchKernelGGL((se_step_kernel<VEC, BF16, HAS_V, true, false, BMAX>), grid, block, 0, stream, a); break;
-    case 2: hipLaunchKernelGGL((se_step_kernel<VEC, BF16, HAS_V, false, true, BMAX>), grid, block, 0, stream, a); break;
-    default: hipLaunchKernelGGL((se_step_kernel<VEC, BF16, HAS_V, true, true, BMAX>), grid, block, 0, stream, a); break;
+    switch (s.block) {
+    case 64: return launch_bs<VEC, BF16, HAS_V, BMAX, 64>(a, s, stream);
+    case 128: return launch_bs<VEC, BF16, HAS_V, BMAX, 128>(a, s, stream);
+    default: return launch_bs<VEC, BF16, HAS_V, BMAX, 256>(a, s, stream);
     }
-    return hipGetLastError();
 }
 
 template <int VEC, bool BF16>

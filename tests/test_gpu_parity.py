@@ -30,7 +30,7 @@ def say(*a):
 @pytest.fixture(autouse=True)
 def _defaults():
     se.se_set_seed(0)
-    saved = {k: se.se_get_tuning(k) for k in ("grid_blocks_per_cu", "group_major", "nontemporal")}
+    saved = {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}
     yield
     se.se_set_seed(0)
     for k, v in saved.items():
@@ -307,11 +307,16 @@ def test_special_values_propagate():
 def test_results_do_not_depend_on_launch_knobs_or_stream():
     ref = None
     stream = torch.cuda.Stream()
-    for bpc, gm, nt, st in [(0, 0, 0, None), (4, 0, 0, None), (1, 1, 0, None), (0, 1, 3, None),
-                            (16, 0, 1, stream), (2, 1, 2, stream)]:
-        se.se_set_tuning("grid_blocks_per_cu", bpc)
-        se.se_set_tuning("group_major", gm)
-        se.se_set_tuning("nontemporal", nt)
+    shapes = [dict(), dict(block_threads=256, max_blocks_per_cu=0, group_major=0, nontemporal=0),
+              dict(block_threads=128, tiles_per_block=3, max_blocks_per_cu=4, nontemporal=1),
+              dict(block_threads=64, tiles_per_block=7, max_blocks_per_cu=1, group_major=0, nontemporal=2),
+              dict(block_threads=256, tiles_per_block=1000, grid_blocks_per_cu=2),
+              dict(block_threads=64, max_blocks_per_cu=32, grid_blocks_per_cu=16)]
+    defaults = {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}
+    for q, shape in enumerate(shapes):
+        for k, val in {**defaults, **shape}.items():
+            se.se_set_tuning(k, val)
+        st = stream if q % 2 else None
         case = Case(16, 70001 * 4, distinct_rows=True, v_std=0.01)
         torch.cuda.synchronize()
         offs = case.offsets()
@@ -331,7 +336,7 @@ def test_results_do_not_depend_on_launch_knobs_or_stream():
                 oracle.ring_step(case.hx, hg, case.hv, 0.1, 0.9)
             case.check("knobs reference")
         else:
-            assert bit_mismatches(got[0], ref[0]) == 0 and bit_mismatches(got[1], ref[1]) == 0
+            assert bit_mismatches(got[0], ref[0]) == 0 and bit_mismatches(got[1], ref[1]) == 0, shape
 
 
 def test_resume_from_any_iteration():
