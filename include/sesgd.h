@@ -131,6 +131,10 @@ int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
  *   "group_major"         se_step block order. 1 (default): all tiles of group 0, then group 1,
  *                         ...; 0: the groups of one tile side by side
  *   "nontemporal"         bit 0: non-temporal loads, bit 1: non-temporal stores (default 3)
+ *   "coop_min_rows"       number of rows reduced together (group_size for se_step, n for
+ *                         se_ring_step) from which the rows are split over the wavefronts of a
+ *                         workgroup and the values to reduce are staged in LDS; below it one
+ *                         wavefront owns all rows of its reduction.  0 = never (default 8)
  *   "grid_blocks_per_cu"  se_ring_step only: grid-stride launch with this many workgroups per
  *                         compute unit; 0 (default) = one workgroup per tile
  * Returns SE_ERR_ARG for an unknown name or a value out of range. */

@@ -31,7 +31,7 @@ EXPORTS = ("se_plan", "se_plan_device", "se_step", "se_step_bf16g", "se_ring_ste
 
 
 TUNING_KNOBS = ("block_threads", "max_blocks_per_cu", "tiles_per_block", "group_major",
-                "nontemporal", "grid_blocks_per_cu")
+                "nontemporal", "grid_blocks_per_cu", "coop_min_rows")
 
 
 class SesgdError(RuntimeError):

@@ -19,7 +19,8 @@ std::atomic<int> g_group_major{1};
 std::atomic<int> g_nontemporal{3};
 std::atomic<int> g_block_threads{64};
 std::atomic<int> g_tiles_per_block{1};
-std::atomic<int> g_max_blocks_per_cu{8};  // step kernel: resident workgroups per CU (0 = no cap)
+std::atomic<int> g_max_blocks_per_cu{8};
+std::atomic<int> g_coop_min_rows{8};      // rows reduced together from which the LDS form is used (0 = never)  // step kernel: resident workgroups per CU (0 = no cap)
 
 thread_local char t_last_error[256] = "";
 
@@ -129,7 +130,15 @@ int step_impl(float *params, const void *grads, float *momentum, const int64_t *
     a.neg_lr = -lr; a.mu = mu; a.inv_m = 1.0f / (float)group_size;
     a.group_major = g_group_major.load();
     s.grid = a.chunks * (uint32_t)a.k;        // < 2^30 / 64 * 64 workgroups
-    const hipError_t e = se::launch_step(a, s, (hipStream_t)stream);
+    const int coop = g_coop_min_rows.load();
+    hipError_t e;
+    if (coop > 0 && group_size >= coop) {
+        a.tiles = (a.nvec + 63u) / 64u;
+        s.grid = a.tiles * (uint32_t)a.k;
+        e = se::launch_coop_step(a, s, (hipStream_t)stream);
+    } else {
+        e = se::launch_step(a, s, (hipStream_t)stream);
+    }
     return e == hipSuccess ? SE_OK : hip_fail("se_step launch", e);
 }
 
@@ -155,7 +164,22 @@ int ring_impl(float *params, const void *grads, float *momentum, const int64_t *
     a.n = n;
     a.neg_lr = -lr; a.mu = mu; a.inv_n = 1.0f / (float)n;
     s.grid = grid_for(a.tiles);
-    const hipError_t e = se::launch_ring(a, s, (hipStream_t)stream);
+    const int coop = g_coop_min_rows.load();
+    hipError_t e;
+    if (coop > 0 && n >= coop) {
+        se::StepArgs c;
+        c.x = params; c.g = grads; c.v = momentum;
+        c.seed = 0; c.iter = 0;
+        c.pitch_bytes = a.pitch_bytes; c.nvec = a.nvec;
+        c.tiles = (a.nvec + 63u) / 64u; c.tiles_per_block = 1; c.chunks = c.tiles;
+        c.n = n; c.m = n; c.k = 1;
+        c.neg_lr = -lr; c.mu = mu; c.inv_m = a.inv_n;
+        c.group_major = 1;
+        s.grid = c.tiles;
+        e = se::launch_coop_ring(c, s, (hipStream_t)stream);
+    } else {
+        e = se::launch_ring(a, s, (hipStream_t)stream);
+    }
     return e == hipSuccess ? SE_OK : hip_fail("se_ring_step launch", e);
 }
 
@@ -277,6 +301,10 @@ int se_set_tuning(const char *name, int value)
         if (value < 0 || value > 32) return SE_ERR_ARG;
         g_max_blocks_per_cu.store(value); return SE_OK;
     }
+    if (!std::strcmp(name, "coop_min_rows")) {
+        if (value < 0 || value > 65) return SE_ERR_ARG;
+        g_coop_min_rows.store(value); return SE_OK;
+    }
     if (!std::strcmp(name, "nontemporal")) {
         if (value < 0 || value > 3) return SE_ERR_ARG;
         g_nontemporal.store(value); return SE_OK;
@@ -293,6 +321,7 @@ int se_get_tuning(const char *name)
     if (!std::strcmp(name, "block_threads")) return g_block_threads.load();
     if (!std::strcmp(name, "tiles_per_block")) return g_tiles_per_block.load();
     if (!std::strcmp(name, "max_blocks_per_cu")) return g_max_blocks_per_cu.load();
+    if (!std::strcmp(name, "coop_min_rows")) return g_coop_min_rows.load();
     return SE_ERR_ARG;
 }
 

@@ -52,6 +52,10 @@ struct LaunchShape {
 
 hipError_t launch_step(const StepArgs &a, const LaunchShape &s, hipStream_t stream);
 hipError_t launch_ring(const RingArgs &a, const LaunchShape &s, hipStream_t stream);
+// cooperative forms: a.m rows reduced together by ceil(a.m / 4) wavefronts per workgroup,
+// a.tiles in tiles of 64 lane-columns, s.grid = a.tiles * a.k (a.k = 1 for the ring)
+hipError_t launch_coop_step(const StepArgs &a, const LaunchShape &s, hipStream_t stream);
+hipError_t launch_coop_ring(const StepArgs &a, const LaunchShape &s, hipStream_t stream);
 hipError_t launch_plan(uint64_t seed, int64_t iter, int n, int m, int32_t *group_of_dev,
                        int32_t *members_dev, hipStream_t stream);
 

@@ -51,10 +51,11 @@ def test_seed_and_tuning_state():
     se.se_set_seed(12345678901234567890)
     assert se.se_get_seed() == 12345678901234567890
     se.se_set_seed(0)
-    assert len(se.TUNING_KNOBS) == 6
+    assert len(se.TUNING_KNOBS) == 7
     for name, good, bad in (("grid_blocks_per_cu", 8, -1), ("group_major", 1, 2),
                             ("nontemporal", 3, 4), ("block_threads", 128, 96),
-                            ("tiles_per_block", 5, 0), ("max_blocks_per_cu", 2, 33)):
+                            ("tiles_per_block", 5, 0), ("max_blocks_per_cu", 2, 33),
+                            ("coop_min_rows", 4, 66)):
         old = se.se_get_tuning(name)
         se.se_set_tuning(name, good)
         assert se.se_get_tuning(name) == good

@@ -311,7 +311,9 @@ def test_results_do_not_depend_on_launch_knobs_or_stream():
               dict(block_threads=128, tiles_per_block=3, max_blocks_per_cu=4, nontemporal=1),
               dict(block_threads=64, tiles_per_block=7, max_blocks_per_cu=1, group_major=0, nontemporal=2),
               dict(block_threads=256, tiles_per_block=1000, grid_blocks_per_cu=2),
-              dict(block_threads=64, max_blocks_per_cu=32, grid_blocks_per_cu=16)]
+              dict(block_threads=64, max_blocks_per_cu=32, grid_blocks_per_cu=16),
+              dict(coop_min_rows=0), dict(coop_min_rows=1), dict(coop_min_rows=2, max_blocks_per_cu=3),
+              dict(coop_min_rows=16, nontemporal=0, group_major=0)]
     defaults = {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}
     for q, shape in enumerate(shapes):
         for k, val in {**defaults, **shape}.items():
@@ -337,6 +339,22 @@ def test_results_do_not_depend_on_launch_knobs_or_stream():
             case.check("knobs reference")
         else:
             assert bit_mismatches(got[0], ref[0]) == 0 and bit_mismatches(got[1], ref[1]) == 0, shape
+
+
+@pytest.mark.parametrize("coop", [0, 1])
+def test_both_kernel_forms_for_every_group_size(coop):
+    """Single-wavefront form (coop_min_rows=0) and LDS-staged form (coop_min_rows=1) of the
+    step and of the ring baseline, each against the oracle, over ragged widths."""
+    se.se_set_tuning("coop_min_rows", coop)
+    for n, m, ncols, dtype in [(64, 64, 777, "f32"), (64, 16, 1030, "bf16"), (24, 6, 515, "f32"),
+                               (9, 3, 64, "f32"), (5, 5, 4, "bf16"), (2, 1, 258, "f32"),
+                               (36, 18, 1, "f32"), (13, 13, 130, "f32")]:
+        case = Case(n, ncols, dtype=dtype, distinct_rows=True, v_std=0.01)
+        run_sesgd(case, m, 2, 0.1, 0.9, 1e-2)
+        case.check(f"coop={coop} step n={n} m={m} cols={ncols} {dtype}")
+        case = Case(n, ncols, dtype=dtype, use_v=(n % 2 == 0), v_std=0.0)
+        run_ring(case, 2, 0.1, 0.9 if n % 2 == 0 else 0.0, 1e-2)
+        case.check(f"coop={coop} ring n={n} cols={ncols} {dtype}")
 
 
 def test_resume_from_any_iteration():
