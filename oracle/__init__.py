@@ -36,23 +36,28 @@ def build(force: bool = True) -> str:
     return _SO
 
 
+def bind(path: str):
+    """Load a build of se_oracle.c and declare its signatures."""
+    lib = ctypes.CDLL(path)
+    i64, u64, i32 = ctypes.c_int64, ctypes.c_uint64, ctypes.c_int
+    vp, f32 = ctypes.c_void_p, ctypes.c_float
+    lib.oracle_key.restype = ctypes.c_uint32
+    lib.oracle_key.argtypes = [u64, i64, i32, i32]
+    lib.oracle_plan.restype = i32
+    lib.oracle_plan.argtypes = [u64, i32, i32, i64, vp, vp, vp, vp]
+    lib.oracle_step.restype = i32
+    lib.oracle_step.argtypes = [vp, vp, i32, vp, i64, i64, i64, i32, i32, u64, i64, f32, f32]
+    lib.oracle_ring_step.restype = i32
+    lib.oracle_ring_step.argtypes = [vp, vp, i32, vp, i64, i64, i64, i32, f32, f32]
+    return lib
+
+
 def _lib():
     global _lib_handle
     with _lock:
         if _lib_handle is None:
             build(force=False)
-            lib = ctypes.CDLL(_SO)
-            i64, u64, i32 = ctypes.c_int64, ctypes.c_uint64, ctypes.c_int
-            vp, f32 = ctypes.c_void_p, ctypes.c_float
-            lib.oracle_key.restype = ctypes.c_uint32
-            lib.oracle_key.argtypes = [u64, i64, i32, i32]
-            lib.oracle_plan.restype = i32
-            lib.oracle_plan.argtypes = [u64, i32, i32, i64, vp, vp, vp, vp]
-            lib.oracle_step.restype = i32
-            lib.oracle_step.argtypes = [vp, vp, i32, vp, i64, i64, i64, i32, i32, u64, i64, f32, f32]
-            lib.oracle_ring_step.restype = i32
-            lib.oracle_ring_step.argtypes = [vp, vp, i32, vp, i64, i64, i64, i32, f32, f32]
-            _lib_handle = lib
+            _lib_handle = bind(_SO)
     return _lib_handle
 
 

@@ -1,0 +1,77 @@
+"""The pins must be able to fail: each plausible mistake planted in a copy of the oracle's C
+source (on the CPU, in a temporary build) has to be caught by at least one pin."""
+import os
+import subprocess
+
+import pytest
+
+import oracle
+import test_oracle_plan as plan_pins
+import test_oracle_step as step_pins
+
+SRC = os.path.join(os.path.dirname(oracle.__file__), "se_oracle.c")
+
+MUTANTS = {
+    "sign of the learning-rate term": ("xhat = fmaf(-lr, vn, params[idx]);", "xhat = fmaf(lr, vn, params[idx]);"),
+    "momentum operands transposed": ("vn = fmaf(mu, momentum[idx], gg);", "vn = fmaf(mu, gg, momentum[idx]);"),
+    "momentum term dropped": ("vn = fmaf(mu, momentum[idx], gg);", "vn = gg;"),
+    "momentum not written back": ("                    momentum[idx] = vn;\n                } else {\n                    vn = gg;",
+                                  "                } else {\n                    vn = gg;"),
+    "learning rate applied to g instead of v'": ("xhat = fmaf(-lr, vn, params[idx]);", "xhat = fmaf(-lr, gg, params[idx]);"),
+    "mean not scaled": ("mean = s * inv_m;", "mean = s;"),
+    "scaled by groups instead of group size": ("inv_m = 1.0f / (float)m;", "inv_m = 1.0f / (float)k;"),
+    "mean written to the first member only": ("params[(int64_t)mem[r] * pitch + e] = mean;", "params[(int64_t)mem[0] * pitch + e] = mean;"),
+    "first member counted twice": ("s = (r == 0) ? xhat : s + xhat;", "s = (r == 0) ? xhat + xhat : s + xhat;"),
+    "unfused multiply-add": ("xhat = fmaf(-lr, vn, params[idx]);", "xhat = params[idx] + (-lr * vn);"),
+    "groups cut by remainder": ("group_of[i] = below / m;", "group_of[i] = below % (n / m);"),
+    "hash shift": ("z ^= z >> 15;", "z ^= z >> 13;"),
+    "hash skips the iteration word": ("w[2] = (uint32_t)(t & 0xFFFFFFFFu);", "w[2] = 0;"),
+    "ring mean not scaled": ("gbar = s * inv_n;", "gbar = s;"),
+    "ring counts worker 0 twice": ("for (i = 1; i < n; ++i)\n            s = s +", "for (i = 0; i < n; ++i)\n            s = s +"),
+    "ring update sign": ("params[idx] = fmaf(-lr, vn, params[idx]);", "params[idx] = fmaf(lr, vn, params[idx]);"),
+}
+
+
+def battery(golden_dir):
+    """A fast subset of the pins; returns the names of those that fail."""
+    checks = [
+        ("worked example", lambda: step_pins.test_worked_example_by_hand(golden_dir)),
+        ("sign/operand", step_pins.test_sign_and_operand_order_are_observable),
+        ("brute n=2", lambda: step_pins.test_brute_force_exact_rational(2)),
+        ("brute n=4", lambda: step_pins.test_brute_force_exact_rational(4)),
+        ("ring brute n=5", lambda: step_pins.test_ring_brute_force_exact_rational(5)),
+        ("conservation", step_pins.test_conservation_of_the_all_worker_sum),
+        ("consensus", step_pins.test_members_of_a_group_end_bit_identical),
+        ("torch sgd", step_pins.test_group_size_one_is_the_library_sgd_optimizer),
+        ("ring = torch", step_pins.test_full_group_is_ring_sgd_is_library_sgd_on_the_mean_gradient),
+        ("no-momentum", step_pins.test_no_momentum_buffer_equals_zero_mu_with_zero_buffer),
+        ("partition n=4", lambda: plan_pins.test_partition_brute_force_small_n(4)),
+        ("keys", plan_pins.test_keys_match_independent_python_implementation),
+        ("seed/iter dependence", plan_pins.test_same_seed_same_plan_and_seed_matters),
+    ]
+    failed = []
+    for name, fn in checks:
+        try:
+            fn()
+        except Exception:            # AssertionError or an oracle error raised by the mutant
+            failed.append(name)
+    return failed
+
+
+def test_unmutated_oracle_passes_the_battery(golden_dir):
+    assert battery(golden_dir) == []
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_planted_mistake_is_caught(name, tmp_path, monkeypatch, golden_dir):
+    old, new = MUTANTS[name]
+    text = open(SRC).read()
+    assert text.count(old) >= 1, f"pattern for '{name}' not found in the oracle source"
+    mutated = text.replace(old, new, 1)
+    c_path, so_path = tmp_path / "mutant.c", tmp_path / "mutant.so"
+    c_path.write_text(mutated)
+    subprocess.run(["gcc", "-O2", "-ffp-contract=off", "-shared", "-fPIC", "-o", str(so_path),
+                    str(c_path), "-lm"], check=True)
+    monkeypatch.setattr(oracle, "_lib_handle", oracle.bind(str(so_path)))
+    failed = battery(golden_dir)
+    assert failed, f"no pin noticed: {name}"
