@@ -49,6 +49,17 @@ def bind(path: str):
     lib.oracle_step.argtypes = [vp, vp, i32, vp, i64, i64, i64, i32, i32, u64, i64, f32, f32]
     lib.oracle_ring_step.restype = i32
     lib.oracle_ring_step.argtypes = [vp, vp, i32, vp, i64, i64, i64, i32, f32, f32]
+    lib.oracle_step_ex.restype = i32
+    lib.oracle_step_ex.argtypes = [vp, vp, i32, vp, i64, i64, i64, i32, i32, u64, i64, f32, f32, f32,
+                                   ctypes.c_uint]
+    lib.oracle_global_average.restype = i32
+    lib.oracle_global_average.argtypes = [vp, i64, i64, i64, i32]
+    lib.oracle_consensus.restype = i32
+    lib.oracle_consensus.argtypes = [vp, i64, i64, i64, i32, vp]
+    lib.oracle_ring_time.restype = ctypes.c_double
+    lib.oracle_ring_time.argtypes = [ctypes.c_double, i32, ctypes.c_double, ctypes.c_double]
+    lib.oracle_handshakes.restype = ctypes.c_long
+    lib.oracle_handshakes.argtypes = [i32, i32]
     return lib
 
 
@@ -133,6 +144,56 @@ def ring_step(params, grads, momentum, lr: float, mu: float, cols=None) -> None:
     rc = _lib().oracle_ring_step(params.ctypes.data, gptr, gbf, mptr, pitch, c0, c1, n, lr, mu)
     if rc != ORACLE_OK:
         raise OracleError(rc)
+
+
+FLAG_GRAD_AVG = 1
+
+
+def step_ex(params, grads, momentum, m: int, it: int, lr: float, mu: float, wd: float = 0.0,
+            flags: int = 0, seed: int = 0, cols=None) -> None:
+    """General step: optional weight decay; flags=FLAG_GRAD_AVG selects the uncorrected
+    variant that averages gradients instead of parameters."""
+    n, pitch = params.shape
+    _check_rows(params, n, "params", (np.float32,))
+    gptr, gbf = _grad_args(grads, n)
+    mptr = None
+    if momentum is not None:
+        _check_rows(momentum, n, "momentum", (np.float32,))
+        mptr = momentum.ctypes.data
+    c0, c1 = (0, pitch) if cols is None else cols
+    rc = _lib().oracle_step_ex(params.ctypes.data, gptr, gbf, mptr, pitch, c0, c1, n, m, seed, it,
+                               lr, mu, wd, flags)
+    if rc != ORACLE_OK:
+        raise OracleError(rc)
+
+
+def global_average(params, cols=None) -> None:
+    n, pitch = params.shape
+    _check_rows(params, n, "params", (np.float32,))
+    c0, c1 = (0, pitch) if cols is None else cols
+    rc = _lib().oracle_global_average(params.ctypes.data, pitch, c0, c1, n)
+    if rc != ORACLE_OK:
+        raise OracleError(rc)
+
+
+def consensus(params, cols=None):
+    """(sum over workers and columns of (x - xbar)^2, sum of all parameters), float64."""
+    n, pitch = params.shape
+    _check_rows(params, n, "params", (np.float32,))
+    c0, c1 = (0, pitch) if cols is None else cols
+    out = np.zeros(2, np.float64)
+    rc = _lib().oracle_consensus(params.ctypes.data, pitch, c0, c1, n, out.ctypes.data)
+    if rc != ORACLE_OK:
+        raise OracleError(rc)
+    return float(out[0]), float(out[1])
+
+
+def ring_time(layer_bytes: float, workers: int, nu: float, t_tau: float) -> float:
+    return float(_lib().oracle_ring_time(layer_bytes, workers, nu, t_tau))
+
+
+def handshakes(layers: int, workers: int) -> int:
+    return int(_lib().oracle_handshakes(layers, workers))
 
 
 def step_threaded(params, grads, momentum, m, it, lr, mu, seed=0, threads=1, ring=False):

@@ -131,3 +131,58 @@ def brute_ring_step(x, g, v, lr, mu):
             if v is not None:
                 v_new[i, e] = np.float32(float(vp))
     return x_new, v_new
+
+
+def brute_step_ex(x, g, v, group_of, m, lr, mu, wd=0.0, grad_avg=False):
+    """General form: weight decay d = wd*x + gsrc folded into the momentum update; with
+    grad_avg the gradients (not the parameters) are averaged inside the group and every
+    worker updates on its own."""
+    n = len(x)
+    P = len(x[0])
+    lr_q, mu_q, wd_q = f32(lr), f32(mu), f32(wd)
+    inv_m = rn32(Fraction(1) / f32(m))
+    x_new = np.zeros((n, P), np.float32)
+    v_new = None if v is None else np.zeros((n, P), np.float32)
+    for e in range(P):
+        if grad_avg:
+            for i in range(n):
+                s = None
+                for j in range(n):
+                    if group_of[j] == group_of[i]:
+                        s = f32(g[j][e]) if s is None else add32(s, f32(g[j][e]))
+                gbar = mul32(s, inv_m)
+                d = gbar if wd_q == 0 else fma32(wd_q, f32(x[i][e]), gbar)
+                vp = d if v is None else fma32(mu_q, f32(v[i][e]), d)
+                x_new[i, e] = np.float32(float(fma32(-lr_q, vp, f32(x[i][e]))))
+                if v is not None:
+                    v_new[i, e] = np.float32(float(vp))
+        else:
+            xhat, vprime = [], []
+            for j in range(n):
+                gg = f32(g[j][e])
+                d = gg if wd_q == 0 else fma32(wd_q, f32(x[j][e]), gg)
+                vp = d if v is None else fma32(mu_q, f32(v[j][e]), d)
+                vprime.append(vp)
+                xhat.append(fma32(-lr_q, vp, f32(x[j][e])))
+            for i in range(n):
+                s = None
+                for j in range(n):
+                    if group_of[j] == group_of[i]:
+                        s = xhat[j] if s is None else add32(s, xhat[j])
+                x_new[i, e] = np.float32(float(mul32(s, inv_m)))
+                if v is not None:
+                    v_new[i, e] = np.float32(float(vprime[i]))
+    return x_new, v_new
+
+
+def brute_global_average(x):
+    n = len(x)
+    P = len(x[0])
+    inv_n = rn32(Fraction(1) / f32(n))
+    out = np.zeros((n, P), np.float32)
+    for e in range(P):
+        s = f32(x[0][e])
+        for j in range(1, n):
+            s = add32(s, f32(x[j][e]))
+        out[:, e] = np.float32(float(mul32(s, inv_n)))
+    return out

@@ -218,3 +218,167 @@ int oracle_ring_step(float *params, const void *grads, int grads_are_bf16, float
     }
     return ORACLE_OK;
 }
+
+/* ------------------------------------------------------------------------------------
+ * Extensions beyond the basic step.  Same conventions as above.
+ * ------------------------------------------------------------------------------------ */
+
+#define ORACLE_FLAG_GRAD_AVG 1u
+
+/*
+ * General step on columns [col_begin, col_end).
+ *
+ * weight_decay (Sec. 4.1 hyper-parameters list 5e-4 / 1e-4; the paper gives no formula, the
+ * convention of the SGD optimizer it names is used): the decayed gradient of worker j is
+ *     d_j = (wd != 0) ? fmaf(wd, x_j, gsrc) : gsrc
+ * and it replaces the gradient in the momentum update.
+ *
+ * flags == 0: the SESGD update (Sec. 3.2 "Gradient Correction"), gsrc = g_j; identical to
+ *   oracle_step when wd == 0.
+ * flags & ORACLE_FLAG_GRAD_AVG: the variant the paper rejects (Sec. 3.2: the shuffle applied
+ *   directly to the DSGD equation).  The *gradients* are averaged inside the group,
+ *     gbar_G = (g_{j0} + g_{j1} + ...) * (1.0f/(float)m)      members ascending, left to right
+ *   and every member updates on its own: gsrc = gbar_G,
+ *     v_j = momentum ? fmaf(mu, v_j, d_j) : d_j ;  x_j = fmaf(-lr, v_j, x_j).
+ *   Parameters are never averaged, so replicas drift apart (the paper's divergence equation).
+ *   With m == n this is exactly oracle_ring_step.
+ */
+int oracle_step_ex(float *params, const void *grads, int grads_are_bf16, float *momentum,
+                   int64_t pitch, int64_t col_begin, int64_t col_end,
+                   int n, int m, uint64_t seed, int64_t iter,
+                   float lr, float mu, float wd, unsigned flags)
+{
+    int32_t group_of[ORACLE_MAX_N];
+    int32_t members[ORACLE_MAX_N];
+    int rc, g, r, k;
+    int64_t e;
+    float inv_m;
+    if (params == NULL || grads == NULL || pitch < 0 || col_begin < 0 ||
+        col_end < col_begin || col_end > pitch || (flags & ~ORACLE_FLAG_GRAD_AVG))
+        return ORACLE_ERR_ARG;
+    rc = oracle_plan(seed, n, m, iter, NULL, NULL, group_of, members);
+    if (rc != ORACLE_OK)
+        return rc;
+    k = n / m;
+    inv_m = 1.0f / (float)m;
+    for (g = 0; g < k; ++g) {
+        const int32_t *mem = members + (size_t)g * m;
+        for (e = col_begin; e < col_end; ++e) {
+            if (flags & ORACLE_FLAG_GRAD_AVG) {
+                float s = 0.0f, gbar;
+                for (r = 0; r < m; ++r) {
+                    float gg = load_grad(grads, grads_are_bf16, (int64_t)mem[r] * pitch + e);
+                    s = (r == 0) ? gg : s + gg;
+                }
+                gbar = s * inv_m;
+                for (r = 0; r < m; ++r) {
+                    int64_t idx = (int64_t)mem[r] * pitch + e;
+                    float d = (wd != 0.0f) ? fmaf(wd, params[idx], gbar) : gbar;
+                    float vn;
+                    if (momentum) {
+                        vn = fmaf(mu, momentum[idx], d);
+                        momentum[idx] = vn;
+                    } else {
+                        vn = d;
+                    }
+                    params[idx] = fmaf(-lr, vn, params[idx]);
+                }
+            } else {
+                float s = 0.0f, mean;
+                for (r = 0; r < m; ++r) {
+                    int64_t idx = (int64_t)mem[r] * pitch + e;
+                    float gg = load_grad(grads, grads_are_bf16, idx);
+                    float d = (wd != 0.0f) ? fmaf(wd, params[idx], gg) : gg;
+                    float vn, xhat;
+                    if (momentum) {
+                        vn = fmaf(mu, momentum[idx], d);
+                        momentum[idx] = vn;
+                    } else {
+                        vn = d;
+                    }
+                    xhat = fmaf(-lr, vn, params[idx]);
+                    s = (r == 0) ? xhat : s + xhat;
+                }
+                mean = s * inv_m;
+                for (r = 0; r < m; ++r)
+                    params[(int64_t)mem[r] * pitch + e] = mean;
+            }
+        }
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * Final global average (Algorithm 1, last line: x-bar <- Ring-AllReduce(x_i; Global)):
+ *   xbar[e] = (x_0[e] + x_1[e] + ... + x_{n-1}[e]) * (1.0f/(float)n), written to every row.
+ */
+int oracle_global_average(float *params, int64_t pitch, int64_t col_begin, int64_t col_end, int n)
+{
+    int i;
+    int64_t e;
+    float inv_n;
+    if (params == NULL || n < 1 || pitch < 0 || col_begin < 0 || col_end < col_begin || col_end > pitch)
+        return ORACLE_ERR_ARG;
+    inv_n = 1.0f / (float)n;
+    for (e = col_begin; e < col_end; ++e) {
+        float s = params[e], mean;
+        for (i = 1; i < n; ++i)
+            s = s + params[(int64_t)i * pitch + e];
+        mean = s * inv_n;
+        for (i = 0; i < n; ++i)
+            params[(int64_t)i * pitch + e] = mean;
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * Replica-consistency diagnostics in double precision (the quantity behind the paper's
+ * divergence equation of Sec. 3.2 and the "consistency of parameters" figure of Sec. 4.2):
+ *   out[0] = sum_e sum_i (x_i[e] - xbar[e])^2   with xbar[e] = (sum_i x_i[e]) / n   (Sec. 3.3)
+ *   out[1] = sum_e sum_i x_i[e]                  (the all-worker parameter sum)
+ * Columns and rows are visited in ascending order.
+ */
+int oracle_consensus(const float *params, int64_t pitch, int64_t col_begin, int64_t col_end,
+                     int n, double *out)
+{
+    int i;
+    int64_t e;
+    double dist = 0.0, total = 0.0;
+    if (params == NULL || out == NULL || n < 1 || pitch < 0 || col_begin < 0 ||
+        col_end < col_begin || col_end > pitch)
+        return ORACLE_ERR_ARG;
+    for (e = col_begin; e < col_end; ++e) {
+        double s = 0.0, mean, d = 0.0;
+        for (i = 0; i < n; ++i)
+            s += (double)params[(int64_t)i * pitch + e];
+        mean = s / (double)n;
+        for (i = 0; i < n; ++i) {
+            double t = (double)params[(int64_t)i * pitch + e] - mean;
+            d += t * t;
+        }
+        dist += d;
+        total += s;
+    }
+    out[0] = dist;
+    out[1] = total;
+    return ORACLE_OK;
+}
+
+/*
+ * Communication-time model of the paper for one layer of G bytes on a network of bandwidth
+ * nu (bytes/s) and latency t_tau (s):
+ *   ring over w workers (Sec. 2.2, the all-reduce cost equation): 2 (w-1) (G/(w nu) + t_tau)
+ * Ring-SGD uses w = n; SESGD with k groups uses w = n/k (Sec. 3.1; with k = sqrt(n) this is
+ * the approximate form 2G/nu + 2 sqrt(n) t_tau of the paper).
+ * handshakes: 2 (w-1) per layer (Sec. 2.3 counts 50 * 2 * 15 = 1500 for 50 layers, n = 16).
+ */
+double oracle_ring_time(double layer_bytes, int workers, double nu, double t_tau)
+{
+    if (workers < 1 || nu <= 0.0) return -1.0;
+    return 2.0 * (double)(workers - 1) * (layer_bytes / ((double)workers * nu) + t_tau);
+}
+
+long oracle_handshakes(int layers, int workers)
+{
+    return (long)layers * 2L * (long)(workers - 1);
+}
