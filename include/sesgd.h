@@ -44,7 +44,7 @@ extern "C" {
 #endif
 
 #define SE_OK                  0
-#define SE_ERR_ARG           (-1)  /* n<1, group_size<1, group_size>n, iter<0, num_layers<0 */
+#define SE_ERR_ARG           (-1)  /* n<1, group_size<1, group_size>n, iter<0, num_layers<0, bad layer range or flags */
 #define SE_ERR_DIVISIBILITY  (-2)  /* n % group_size != 0: the paper defines equal groups only */
 #define SE_ERR_NULL          (-3)  /* a required pointer is NULL */
 #define SE_ERR_LAYOUT        (-4)  /* offsets not monotone, offsets[0]!=0, buffers overlap, misaligned */
@@ -104,6 +104,63 @@ int se_ring_step_bf16g(float *params, const uint16_t *grads_bf16, float *momentu
                        const int64_t *layer_offsets, int num_layers,
                        int n, float lr, float mu, void *stream);
 
+/*
+ * General form of the step.
+ *   grads_are_bf16  0: grads points at fp32, else at bfloat16 bit patterns
+ *   first_layer, last_layer   only columns layer_offsets[first_layer] .. layer_offsets[last_layer]
+ *                   of every row are stepped (0 <= first_layer <= last_layer <= num_layers).
+ *                   The paper sends layer l while backward computes layer l-1 (Sec. 2.1); a
+ *                   caller reproduces that schedule with one call per layer range.  The groups
+ *                   depend on iter only, so stepping every layer once with the same iter equals
+ *                   one se_step.
+ *   weight_decay    (Sec. 4.1 lists 5e-4 / 1e-4) folded into the momentum update as the
+ *                   decayed gradient d = fma(weight_decay, x, g); 0 means none (d = g).
+ *   flags           0: the SESGD update (Sec. 3.2 "Gradient Correction").
+ *                   SE_FLAG_GRAD_AVG: the variant the paper rejects (Sec. 3.2, the shuffle
+ *                   applied directly to the DSGD equation): the gradients are averaged inside
+ *                   the group, gbar = (g_j0 + g_j1 + ...) * (1.0f/(float)group_size), and every
+ *                   member updates on its own with d = fma(weight_decay, x_j, gbar),
+ *                   v_j = fma(mu, v_j, d), x_j = fma(-lr, v_j, x_j).  Replicas drift apart.
+ *                   With group_size == n this is se_ring_step.
+ * Local-SGD / Local-SESGD (Sec. 4.1 baselines: synchronise every second iteration) need no
+ * flag: an iteration without synchronisation is a call with group_size == 1.
+ */
+#define SE_FLAG_GRAD_AVG 1u
+int se_step_ex(float *params, const void *grads, int grads_are_bf16, float *momentum,
+               const int64_t *layer_offsets, int num_layers, int first_layer, int last_layer,
+               int n, int group_size, int64_t iter, float lr, float mu, float weight_decay,
+               unsigned flags, void *stream);
+
+/* Final global average (Algorithm 1, last line): every row of params becomes
+ * (x_0 + x_1 + ... + x_{n-1}) * (1.0f/(float)n), summed left to right.  Reads and writes
+ * params only. */
+int se_global_average(float *params, const int64_t *layer_offsets, int num_layers, int n,
+                      void *stream);
+
+/*
+ * Replica-consistency diagnostics in double precision (the quantity of the divergence equation
+ * of Sec. 3.2 and of the parameter-consistency experiment of Sec. 4.2; xbar as in Sec. 3.3):
+ *   out_dev[0] = sum over columns e and workers i of (x_i[e] - xbar[e])^2, xbar[e] = mean_i x_i[e]
+ *   out_dev[1] = sum of all n*pitch parameters
+ * out_dev is a DEVICE array of two doubles, 8-byte aligned, written on `stream` (cleared by the
+ * call itself).  The summation order over columns is not fixed: results agree with a
+ * sequential evaluation to about 1e-13 relative; identical replicas give exactly 0.
+ */
+int se_consensus(const float *params, const int64_t *layer_offsets, int num_layers, int n,
+                 double *out_dev, void *stream);
+
+/*
+ * Host-only calculator of the paper's communication-time model, to set a simulated step beside
+ * the paper's cluster setting.  For every layer of G bytes (element count from layer_offsets
+ * times elem_bytes), a ring all-reduce over w workers costs 2 (w-1) (G/(w*bandwidth) + latency)
+ * seconds and 2 (w-1) handshakes (Sec. 2.2); Ring-SGD uses w = n, SESGD with `groups` groups
+ * uses w = n/groups (Sec. 3.1).  bandwidth in bytes/s, latency in seconds.  Any output pointer
+ * may be NULL.  Touches no device.
+ */
+int se_comm_model(const int64_t *layer_offsets, int num_layers, int elem_bytes, int n, int groups,
+                  double bandwidth, double latency, double *ring_seconds, double *sesgd_seconds,
+                  int64_t *ring_handshakes, int64_t *sesgd_handshakes);
+
 /* The shared random seed of Algorithm 1 (process-wide, default 0).  Read at call time by
  * se_plan, se_plan_device and se_step. */
 int      se_set_seed(uint64_t seed);
@@ -124,19 +181,16 @@ int64_t se_step_bytes(int64_t pitch, int n, int grad_elem_bytes, int has_momentu
 int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
 
 /* Launch-shape knobs for measurement sweeps; results never depend on them.
- *   "block_threads"       threads per workgroup: 64 (default), 128 or 256
  *   "max_blocks_per_cu"   cap on resident workgroups per compute unit, enforced by requesting
  *                         160 KiB / cap of (unused) LDS per workgroup; 0 = no cap (default 8)
- *   "tiles_per_block"     consecutive tiles one workgroup of se_step walks through (default 1)
- *   "group_major"         se_step block order. 1 (default): all tiles of group 0, then group 1,
- *                         ...; 0: the groups of one tile side by side
- *   "nontemporal"         bit 0: non-temporal loads, bit 1: non-temporal stores (default 3)
- *   "coop_min_rows"       number of rows reduced together (group_size for se_step, n for
- *                         se_ring_step) from which the rows are split over the wavefronts of a
- *                         workgroup and the values to reduce are staged in LDS; below it one
- *                         wavefront owns all rows of its reduction.  0 = never (default 8)
- *   "grid_blocks_per_cu"  se_ring_step only: grid-stride launch with this many workgroups per
- *                         compute unit; 0 (default) = one workgroup per tile
+ *   "tiles_per_block"     consecutive 64-lane tiles one workgroup walks through (default 1)
+ *   "group_major"         block order. 1 (default): all tiles of group 0, then group 1, ...;
+ *                         0: the groups of one tile side by side
+ *   "nontemporal"         1 (default): streaming (non-temporal) loads and stores; 0: plain
+ *   "coop_min_rows"       number of rows reduced together (group_size; n for se_ring_step and
+ *                         se_global_average) from which the rows are split over the wavefronts
+ *                         of a workgroup and the values to reduce are staged in LDS; below it
+ *                         one wavefront owns all rows of its group.  0 = never (default 8)
  * Returns SE_ERR_ARG for an unknown name or a value out of range. */
 int se_set_tuning(const char *name, int value);
 int se_get_tuning(const char *name);

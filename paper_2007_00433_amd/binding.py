@@ -27,11 +27,13 @@ SE_MAX_WORKERS = 64
 
 EXPORTS = ("se_plan", "se_plan_device", "se_step", "se_step_bf16g", "se_ring_step",
            "se_ring_step_bf16g", "se_set_seed", "se_get_seed", "se_pitch", "se_step_bytes",
-           "se_set_tuning", "se_get_tuning", "se_strerror", "se_last_error", "se_calib_copy")
+           "se_set_tuning", "se_get_tuning", "se_strerror", "se_last_error", "se_calib_copy",
+           "se_step_ex", "se_global_average", "se_consensus", "se_comm_model")
 
 
-TUNING_KNOBS = ("block_threads", "max_blocks_per_cu", "tiles_per_block", "group_major",
-                "nontemporal", "grid_blocks_per_cu", "coop_min_rows")
+SE_FLAG_GRAD_AVG = 1
+TUNING_KNOBS = ("max_blocks_per_cu", "tiles_per_block", "group_major", "nontemporal",
+                "coop_min_rows")
 
 
 class SesgdError(RuntimeError):
@@ -78,6 +80,16 @@ def _load() -> ctypes.CDLL:
     lib.se_set_tuning.argtypes = [cp, i32]
     lib.se_get_tuning.restype = i32
     lib.se_get_tuning.argtypes = [cp]
+    lib.se_step_ex.restype = i32
+    lib.se_step_ex.argtypes = [vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i64, f32, f32, f32,
+                               ctypes.c_uint, vp]
+    lib.se_global_average.restype = i32
+    lib.se_global_average.argtypes = [vp, vp, i32, i32, vp]
+    lib.se_consensus.restype = i32
+    lib.se_consensus.argtypes = [vp, vp, i32, i32, vp, vp]
+    lib.se_comm_model.restype = i32
+    lib.se_comm_model.argtypes = [vp, i32, i32, i32, i32, ctypes.c_double, ctypes.c_double,
+                                  vp, vp, vp, vp]
     lib.se_calib_copy.restype = i32
     lib.se_calib_copy.argtypes = [vp, vp, i64, vp]
     lib.se_strerror.restype = cp
@@ -222,3 +234,47 @@ def se_ring_step_bf16g(params, grads_bf16, momentum, layer_offsets, n: int, lr: 
     offs = _offsets(layer_offsets)
     check(lib.se_ring_step_bf16g(_ptr(params), _ptr(grads_bf16), _ptr(momentum),
                                  offs.ctypes.data, len(offs) - 1, n, lr, mu, _stream(stream)))
+
+
+def se_step_ex_raw(params, grads, grads_are_bf16, momentum, layer_offsets, num_layers, first_layer,
+                   last_layer, n, group_size, it, lr, mu, weight_decay, flags, stream) -> int:
+    offs = None if layer_offsets is None else _offsets(layer_offsets)
+    return int(lib.se_step_ex(_ptr(params), _ptr(grads), int(grads_are_bf16), _ptr(momentum),
+                              None if offs is None else offs.ctypes.data, num_layers, first_layer,
+                              last_layer, n, group_size, it, lr, mu, weight_decay, flags,
+                              _stream(stream)))
+
+
+def se_step_ex(params, grads, momentum, layer_offsets, n: int, group_size: int, it: int,
+               lr: float, mu: float, weight_decay: float = 0.0, flags: int = 0,
+               first_layer: int = 0, last_layer: Optional[int] = None,
+               grads_are_bf16: bool = False, stream=None) -> None:
+    offs = _offsets(layer_offsets)
+    last = len(offs) - 1 if last_layer is None else last_layer
+    check(lib.se_step_ex(_ptr(params), _ptr(grads), int(grads_are_bf16), _ptr(momentum),
+                         offs.ctypes.data, len(offs) - 1, first_layer, last, n, group_size, it,
+                         lr, mu, weight_decay, flags, _stream(stream)))
+
+
+def se_global_average(params, layer_offsets, n: int, stream=None) -> None:
+    offs = _offsets(layer_offsets)
+    check(lib.se_global_average(_ptr(params), offs.ctypes.data, len(offs) - 1, n, _stream(stream)))
+
+
+def se_consensus(params, layer_offsets, n: int, out_dev, stream=None) -> None:
+    """out_dev: device tensor of two float64 (distance to the mean, sum of parameters)."""
+    offs = _offsets(layer_offsets)
+    check(lib.se_consensus(_ptr(params), offs.ctypes.data, len(offs) - 1, n, _ptr(out_dev),
+                           _stream(stream)))
+
+
+def se_comm_model(layer_offsets, elem_bytes: int, n: int, groups: int, bandwidth: float,
+                  latency: float) -> dict:
+    offs = _offsets(layer_offsets)
+    ring, sesgd = ctypes.c_double(), ctypes.c_double()
+    rh, sh = ctypes.c_int64(), ctypes.c_int64()
+    check(lib.se_comm_model(offs.ctypes.data, len(offs) - 1, elem_bytes, n, groups, bandwidth,
+                            latency, ctypes.addressof(ring), ctypes.addressof(sesgd),
+                            ctypes.addressof(rh), ctypes.addressof(sh)))
+    return {"ring_seconds": ring.value, "sesgd_seconds": sesgd.value,
+            "ring_handshakes": rh.value, "sesgd_handshakes": sh.value}

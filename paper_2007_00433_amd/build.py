@@ -14,7 +14,8 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsesgd.so")
-SOURCES = ["se_api.cpp", "se_plan.hip", "se_step.hip", "se_ring.hip", "se_coop.hip", "se_calib.hip"]
+SOURCES = ["se_api.cpp", "se_plan.hip", "se_step.hip", "se_coop.hip", "se_consensus.hip",
+           "se_calib.hip"]
 
 HIP_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

@@ -7,20 +7,17 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
-#include <mutex>
 
 #include "../../include/sesgd.h"
 
 namespace {
 
 std::atomic<uint64_t> g_seed{0};
-std::atomic<int> g_blocks_per_cu{0};     // ring kernel: grid-stride blocks per CU (0 = one per tile)
 std::atomic<int> g_group_major{1};
-std::atomic<int> g_nontemporal{3};
-std::atomic<int> g_block_threads{64};
+std::atomic<int> g_nontemporal{1};
 std::atomic<int> g_tiles_per_block{1};
-std::atomic<int> g_max_blocks_per_cu{8};
-std::atomic<int> g_coop_min_rows{8};      // rows reduced together from which the LDS form is used (0 = never)  // step kernel: resident workgroups per CU (0 = no cap)
+std::atomic<int> g_max_blocks_per_cu{8};  // resident workgroups per CU (0 = no cap)
+std::atomic<int> g_coop_min_rows{8};      // rows reduced together from which the LDS form is used (0 = never)
 
 thread_local char t_last_error[256] = "";
 
@@ -30,22 +27,6 @@ int hip_fail(const char *what, hipError_t e)
     return SE_ERR_HIP;
 }
 
-int compute_units()
-{
-    static std::mutex mu;
-    static int cached[64];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    std::lock_guard<std::mutex> lock(mu);
-    if (cached[dev] == 0) {
-        int cus = 0;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-            cus = 256;
-        cached[dev] = cus;
-    }
-    return cached[dev];
-}
-
 bool overlaps(const void *a, uint64_t abytes, const void *b, uint64_t bbytes)
 {
     if (!a || !b || abytes == 0 || bbytes == 0) return false;
@@ -53,19 +34,15 @@ bool overlaps(const void *a, uint64_t abytes, const void *b, uint64_t bbytes)
     return a0 < b0 + bbytes && b0 < a0 + abytes;
 }
 
-struct Layout {
-    int64_t pitch;
-    int vec;
-};
-
-// Everything that can be rejected without touching the device.
+// Everything that can be rejected without touching the device.  grads may be NULL only when
+// grad_bytes == 0 (calls that take no gradients).
 int validate(const void *params, const void *grads, const void *momentum,
              const int64_t *layer_offsets, int num_layers, int n, int group_size, int64_t iter,
-             float mu, int grad_bytes, Layout *out)
+             float mu, int grad_bytes, int64_t *pitch_out)
 {
     if (n < 1 || group_size < 1 || group_size > n || iter < 0 || num_layers < 0) return SE_ERR_ARG;
     if (n % group_size != 0) return SE_ERR_DIVISIBILITY;
-    if (!params || !grads || !layer_offsets) return SE_ERR_NULL;
+    if (!params || !layer_offsets || (grad_bytes && !grads)) return SE_ERR_NULL;
     if (!momentum && mu != 0.0f) return SE_ERR_NULL;
     if (layer_offsets[0] != 0) return SE_ERR_LAYOUT;
     for (int l = 0; l < num_layers; ++l)
@@ -73,114 +50,104 @@ int validate(const void *params, const void *grads, const void *momentum,
     const int64_t pitch = layer_offsets[num_layers];
     if (n > SE_MAX_WORKERS || pitch >= ((int64_t)1 << 30)) return SE_ERR_UNSUPPORTED;
     const uintptr_t px = (uintptr_t)params, pg = (uintptr_t)grads, pv = (uintptr_t)momentum;
-    if (px % 4 || pv % 4 || pg % (uintptr_t)grad_bytes) return SE_ERR_LAYOUT;
+    if (px % 4 || pv % 4 || (grad_bytes && pg % (uintptr_t)grad_bytes)) return SE_ERR_LAYOUT;
     const uint64_t fbytes = (uint64_t)n * (uint64_t)pitch * 4u;
     const uint64_t gbytes = (uint64_t)n * (uint64_t)pitch * (uint64_t)grad_bytes;
     if (overlaps(params, fbytes, grads, gbytes) || overlaps(params, fbytes, momentum, fbytes) ||
         overlaps(grads, gbytes, momentum, fbytes))
         return SE_ERR_LAYOUT;
-    // widest access for which every row of every buffer starts aligned
-    int vec = 1;
-    for (int cand = 4; cand > 1; cand >>= 1) {
-        const uintptr_t fa = (uintptr_t)cand * 4u, ga = (uintptr_t)cand * (uintptr_t)grad_bytes;
-        if (pitch % cand == 0 && px % fa == 0 && pv % fa == 0 && pg % ga == 0) { vec = cand; break; }
-    }
-    out->pitch = pitch;
-    out->vec = vec;
+    *pitch_out = pitch;
     return SE_OK;
 }
 
-uint32_t grid_for(uint64_t ntasks)
-{
-    const int bpc = g_blocks_per_cu.load();
-    uint64_t grid = ntasks;
-    if (bpc > 0) {
-        const uint64_t cap = (uint64_t)compute_units() * (uint64_t)bpc;
-        if (grid > cap) grid = cap;
-    }
-    if (grid > 0x7FFFFFFFull) grid = 0x7FFFFFFFull;
-    return (uint32_t)grid;
-}
+struct Job {
+    float *x;
+    const void *g;
+    float *v;
+    int grad_bytes;          // 4, 2, or 0 when the mode reads no gradients
+    int64_t pitch;
+    int n, m;
+    int64_t iter;
+    float lr, mu, wd;
+    int mode;
+    hipStream_t stream;
+};
 
-int step_impl(float *params, const void *grads, float *momentum, const int64_t *layer_offsets,
-              int num_layers, int n, int group_size, int64_t iter, float lr, float mu,
-              void *stream, int grad_bytes)
+// One launch over columns [c0, c1) with `vec` columns per lane; (c1 - c0) % vec == 0 and every
+// row of every buffer is vec-aligned at column c0.
+hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
 {
-    Layout lay;
-    const int rc = validate(params, grads, momentum, layer_offsets, num_layers, n, group_size,
-                            iter, mu, grad_bytes, &lay);
-    if (rc != SE_OK) return rc;
-    if (lay.pitch == 0) return SE_OK;
-
+    if (c1 <= c0) return hipSuccess;
     se::StepArgs a;
-    a.x = params; a.g = grads; a.v = momentum;
-    a.seed = g_seed.load(); a.iter = iter;
-    a.pitch_bytes = (uint64_t)lay.pitch * 4u;
-    se::LaunchShape s;
-    s.vec = lay.vec; s.bf16 = grad_bytes == 2; s.nontemporal = g_nontemporal.load();
-    s.block = g_block_threads.load();
-    const int cap = g_max_blocks_per_cu.load();
-    s.lds_bytes = cap > 0 ? (se::kLdsPerCu / (uint32_t)cap) & ~1023u : 0u;
-
-    a.nvec = (uint32_t)(lay.pitch / lay.vec);
-    a.tiles = (a.nvec + (uint32_t)s.block - 1) / (uint32_t)s.block;
+    a.x = j.x + c0;
+    a.g = j.g ? (const void *)((const char *)j.g + c0 * j.grad_bytes) : nullptr;
+    a.v = j.v ? j.v + c0 : nullptr;
+    a.seed = g_seed.load();
+    a.iter = j.iter;
+    a.pitch_bytes = (uint64_t)j.pitch * 4u;
+    a.nvec = (uint32_t)((c1 - c0) / vec);
+    a.tiles = (a.nvec + 63u) / 64u;
     a.tiles_per_block = (uint32_t)g_tiles_per_block.load();
     a.chunks = (a.tiles + a.tiles_per_block - 1) / a.tiles_per_block;
-    a.n = n; a.m = group_size; a.k = n / group_size;
-    a.neg_lr = -lr; a.mu = mu; a.inv_m = 1.0f / (float)group_size;
+    a.n = j.n; a.m = j.m; a.k = j.n / j.m;
+    a.neg_lr = -j.lr; a.mu = j.mu; a.inv_m = 1.0f / (float)j.m; a.wd = j.wd;
+    a.mode = j.mode;
     a.group_major = g_group_major.load();
-    s.grid = a.chunks * (uint32_t)a.k;        // < 2^30 / 64 * 64 workgroups
-    const int coop = g_coop_min_rows.load();
-    hipError_t e;
-    if (coop > 0 && group_size >= coop) {
-        a.tiles = (a.nvec + 63u) / 64u;
-        s.grid = a.tiles * (uint32_t)a.k;
-        e = se::launch_coop_step(a, s, (hipStream_t)stream);
-    } else {
-        e = se::launch_step(a, s, (hipStream_t)stream);
-    }
-    return e == hipSuccess ? SE_OK : hip_fail("se_step launch", e);
-}
 
-int ring_impl(float *params, const void *grads, float *momentum, const int64_t *layer_offsets,
-              int num_layers, int n, float lr, float mu, void *stream, int grad_bytes)
-{
-    Layout lay;
-    const int rc = validate(params, grads, momentum, layer_offsets, num_layers, n, 1, 0, mu,
-                            grad_bytes, &lay);
-    if (rc != SE_OK) return rc;
-    if (lay.pitch == 0) return SE_OK;
-
-    se::RingArgs a;
-    a.x = params; a.g = grads; a.v = momentum;
-    a.pitch_bytes = (uint64_t)lay.pitch * 4u;
     se::LaunchShape s;
-    s.vec = lay.vec; s.bf16 = grad_bytes == 2; s.nontemporal = g_nontemporal.load();
-    s.block = g_block_threads.load();
+    s.vec = vec;
+    s.bf16 = j.grad_bytes == 2;
+    s.nontemporal = g_nontemporal.load() != 0;
     const int cap = g_max_blocks_per_cu.load();
     s.lds_bytes = cap > 0 ? (se::kLdsPerCu / (uint32_t)cap) & ~1023u : 0u;
-    a.nvec = (uint32_t)(lay.pitch / lay.vec);
-    a.tiles = (a.nvec + (uint32_t)s.block - 1) / (uint32_t)s.block;
-    a.n = n;
-    a.neg_lr = -lr; a.mu = mu; a.inv_n = 1.0f / (float)n;
-    s.grid = grid_for(a.tiles);
     const int coop = g_coop_min_rows.load();
-    hipError_t e;
-    if (coop > 0 && n >= coop) {
-        se::StepArgs c;
-        c.x = params; c.g = grads; c.v = momentum;
-        c.seed = 0; c.iter = 0;
-        c.pitch_bytes = a.pitch_bytes; c.nvec = a.nvec;
-        c.tiles = (a.nvec + 63u) / 64u; c.tiles_per_block = 1; c.chunks = c.tiles;
-        c.n = n; c.m = n; c.k = 1;
-        c.neg_lr = -lr; c.mu = mu; c.inv_m = a.inv_n;
-        c.group_major = 1;
-        s.grid = c.tiles;
-        e = se::launch_coop_ring(c, s, (hipStream_t)stream);
-    } else {
-        e = se::launch_ring(a, s, (hipStream_t)stream);
+    if (coop > 0 && j.m >= coop) {
+        s.grid = a.tiles * (uint32_t)a.k;              // < 2^24 * 64
+        return se::launch_coop(a, s, j.stream);
     }
-    return e == hipSuccess ? SE_OK : hip_fail("se_ring_step launch", e);
+    s.grid = a.chunks * (uint32_t)a.k;
+    return se::launch_step(a, s, j.stream);
+}
+
+// Columns [c0, c1) of every row: the widest aligned body plus scalar head and tail columns.
+hipError_t launch_range(const Job &j, int64_t c0, int64_t c1)
+{
+    if (c1 <= c0) return hipSuccess;
+    const int gb = j.grad_bytes ? j.grad_bytes : 4;
+    const uintptr_t ex = (uintptr_t)j.x / 4u;                       // base addresses in elements
+    const uintptr_t ev = j.v ? (uintptr_t)j.v / 4u : ex;
+    const uintptr_t eg = j.g ? (uintptr_t)j.g / (uintptr_t)gb : ex;
+    for (int vec = 4; vec > 1; vec >>= 1) {
+        const uintptr_t v = (uintptr_t)vec;
+        if (j.pitch % vec != 0 || ex % v != ev % v || ex % v != eg % v) continue;
+        const int64_t head = (int64_t)((v - (ex + (uintptr_t)c0) % v) % v);   // columns up to alignment
+        const int64_t a = c0 + head;
+        if (a >= c1) break;
+        const int64_t b = a + (c1 - a) / vec * vec;
+        if (b <= a) continue;
+        hipError_t e = launch_columns(j, c0, a, 1);
+        if (e == hipSuccess) e = launch_columns(j, a, b, vec);
+        if (e == hipSuccess) e = launch_columns(j, b, c1, 1);
+        return e;
+    }
+    return launch_columns(j, c0, c1, 1);
+}
+
+int run(const char *what, float *params, const void *grads, int grad_bytes, float *momentum,
+        const int64_t *layer_offsets, int num_layers, int first_layer, int last_layer,
+        int n, int group_size, int64_t iter, float lr, float mu, float wd, int mode, void *stream)
+{
+    int64_t pitch = 0;
+    const int rc = validate(params, grads, momentum, layer_offsets, num_layers, n, group_size,
+                            iter, mu, grad_bytes, &pitch);
+    if (rc != SE_OK) return rc;
+    if (first_layer < 0 || last_layer < first_layer || last_layer > num_layers) return SE_ERR_ARG;
+    Job j;
+    j.x = params; j.g = grads; j.v = momentum; j.grad_bytes = grad_bytes;
+    j.pitch = pitch; j.n = n; j.m = group_size; j.iter = iter;
+    j.lr = lr; j.mu = mu; j.wd = wd; j.mode = mode; j.stream = (hipStream_t)stream;
+    const hipError_t e = launch_range(j, layer_offsets[first_layer], layer_offsets[last_layer]);
+    return e == hipSuccess ? SE_OK : hip_fail(what, e);
 }
 
 int plan_check(int n, int group_size, int64_t iter, const void *group_of)
@@ -191,6 +158,15 @@ int plan_check(int n, int group_size, int64_t iter, const void *group_of)
     if (n > SE_MAX_WORKERS) return SE_ERR_UNSUPPORTED;
     return SE_OK;
 }
+
+struct Knob { const char *name; std::atomic<int> *value; int lo, hi; };
+Knob kKnobs[] = {
+    {"max_blocks_per_cu", &g_max_blocks_per_cu, 0, 32},
+    {"tiles_per_block", &g_tiles_per_block, 1, 65536},
+    {"group_major", &g_group_major, 0, 1},
+    {"nontemporal", &g_nontemporal, 0, 1},
+    {"coop_min_rows", &g_coop_min_rows, 0, 65},
+};
 
 }  // namespace
 
@@ -226,29 +202,92 @@ int se_plan_device(int n, int group_size, int64_t iter, int32_t *group_of_dev,
 int se_step(float *params, const float *grads, float *momentum, const int64_t *layer_offsets,
             int num_layers, int n, int group_size, int64_t iter, float lr, float mu, void *stream)
 {
-    return step_impl(params, grads, momentum, layer_offsets, num_layers, n, group_size, iter,
-                     lr, mu, stream, 4);
+    return run("se_step launch", params, grads, 4, momentum, layer_offsets, num_layers, 0,
+               num_layers, n, group_size, iter, lr, mu, 0.0f, se::kSesgd, stream);
 }
 
 int se_step_bf16g(float *params, const uint16_t *grads_bf16, float *momentum,
                   const int64_t *layer_offsets, int num_layers, int n, int group_size,
                   int64_t iter, float lr, float mu, void *stream)
 {
-    return step_impl(params, grads_bf16, momentum, layer_offsets, num_layers, n, group_size,
-                     iter, lr, mu, stream, 2);
+    return run("se_step_bf16g launch", params, grads_bf16, 2, momentum, layer_offsets, num_layers,
+               0, num_layers, n, group_size, iter, lr, mu, 0.0f, se::kSesgd, stream);
 }
 
+int se_step_ex(float *params, const void *grads, int grads_are_bf16, float *momentum,
+               const int64_t *layer_offsets, int num_layers, int first_layer, int last_layer,
+               int n, int group_size, int64_t iter, float lr, float mu, float weight_decay,
+               unsigned flags, void *stream)
+{
+    if (flags & ~(unsigned)SE_FLAG_GRAD_AVG) return SE_ERR_ARG;
+    return run("se_step_ex launch", params, grads, grads_are_bf16 ? 2 : 4, momentum, layer_offsets,
+               num_layers, first_layer, last_layer, n, group_size, iter, lr, mu, weight_decay,
+               (flags & SE_FLAG_GRAD_AVG) ? se::kGradAvg : se::kSesgd, stream);
+}
+
+// Ring-SGD is the gradient-averaging form with a single group of all n workers.
 int se_ring_step(float *params, const float *grads, float *momentum, const int64_t *layer_offsets,
                  int num_layers, int n, float lr, float mu, void *stream)
 {
-    return ring_impl(params, grads, momentum, layer_offsets, num_layers, n, lr, mu, stream, 4);
+    return run("se_ring_step launch", params, grads, 4, momentum, layer_offsets, num_layers, 0,
+               num_layers, n, n < 1 ? 1 : n, 0, lr, mu, 0.0f, se::kGradAvg, stream);
 }
 
 int se_ring_step_bf16g(float *params, const uint16_t *grads_bf16, float *momentum,
                        const int64_t *layer_offsets, int num_layers, int n, float lr, float mu,
                        void *stream)
 {
-    return ring_impl(params, grads_bf16, momentum, layer_offsets, num_layers, n, lr, mu, stream, 2);
+    return run("se_ring_step_bf16g launch", params, grads_bf16, 2, momentum, layer_offsets,
+               num_layers, 0, num_layers, n, n < 1 ? 1 : n, 0, lr, mu, 0.0f, se::kGradAvg, stream);
+}
+
+int se_global_average(float *params, const int64_t *layer_offsets, int num_layers, int n,
+                      void *stream)
+{
+    return run("se_global_average launch", params, nullptr, 0, nullptr, layer_offsets, num_layers,
+               0, num_layers, n, n < 1 ? 1 : n, 0, 0.0f, 0.0f, 0.0f, se::kAvgOnly, stream);
+}
+
+int se_consensus(const float *params, const int64_t *layer_offsets, int num_layers, int n,
+                 double *out_dev, void *stream)
+{
+    int64_t pitch = 0;
+    const int rc = validate(params, nullptr, nullptr, layer_offsets, num_layers, n, 1, 0, 0.0f, 0,
+                            &pitch);
+    if (rc != SE_OK) return rc;
+    if (!out_dev) return SE_ERR_NULL;
+    if ((uintptr_t)out_dev % 8 ||
+        overlaps(params, (uint64_t)n * (uint64_t)pitch * 4u, out_dev, 16))
+        return SE_ERR_LAYOUT;
+    const hipError_t e = se::launch_consensus(params, (uint64_t)pitch, (uint64_t)pitch, n, out_dev,
+                                              (hipStream_t)stream);
+    return e == hipSuccess ? SE_OK : hip_fail("se_consensus launch", e);
+}
+
+int se_comm_model(const int64_t *layer_offsets, int num_layers, int elem_bytes, int n, int groups,
+                  double bandwidth, double latency, double *ring_seconds, double *sesgd_seconds,
+                  int64_t *ring_handshakes, int64_t *sesgd_handshakes)
+{
+    if (num_layers < 0 || elem_bytes < 1 || n < 1 || groups < 1 || !(bandwidth > 0.0) ||
+        !(latency >= 0.0))
+        return SE_ERR_ARG;
+    if (n % groups != 0) return SE_ERR_DIVISIBILITY;
+    if (!layer_offsets) return SE_ERR_NULL;
+    if (layer_offsets[0] != 0) return SE_ERR_LAYOUT;
+    for (int l = 0; l < num_layers; ++l)
+        if (layer_offsets[l + 1] < layer_offsets[l]) return SE_ERR_LAYOUT;
+    const int m = n / groups;
+    double ring = 0.0, se_t = 0.0;
+    for (int l = 0; l < num_layers; ++l) {
+        const double bytes = (double)(layer_offsets[l + 1] - layer_offsets[l]) * (double)elem_bytes;
+        ring += 2.0 * (double)(n - 1) * (bytes / ((double)n * bandwidth) + latency);
+        se_t += 2.0 * (double)(m - 1) * (bytes / ((double)m * bandwidth) + latency);
+    }
+    if (ring_seconds) *ring_seconds = ring;
+    if (sesgd_seconds) *sesgd_seconds = se_t;
+    if (ring_handshakes) *ring_handshakes = (int64_t)num_layers * 2 * (n - 1);
+    if (sesgd_handshakes) *sesgd_handshakes = (int64_t)num_layers * 2 * (m - 1);
+    return SE_OK;
 }
 
 int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream)
@@ -281,33 +320,11 @@ int64_t se_step_bytes(int64_t pitch, int n, int grad_elem_bytes, int has_momentu
 int se_set_tuning(const char *name, int value)
 {
     if (!name) return SE_ERR_NULL;
-    if (!std::strcmp(name, "grid_blocks_per_cu")) {
-        if (value < 0 || value > 4096) return SE_ERR_ARG;
-        g_blocks_per_cu.store(value); return SE_OK;
-    }
-    if (!std::strcmp(name, "group_major")) {
-        if (value < 0 || value > 1) return SE_ERR_ARG;
-        g_group_major.store(value); return SE_OK;
-    }
-    if (!std::strcmp(name, "block_threads")) {
-        if (value != 64 && value != 128 && value != 256) return SE_ERR_ARG;
-        g_block_threads.store(value); return SE_OK;
-    }
-    if (!std::strcmp(name, "tiles_per_block")) {
-        if (value < 1 || value > 65536) return SE_ERR_ARG;
-        g_tiles_per_block.store(value); return SE_OK;
-    }
-    if (!std::strcmp(name, "max_blocks_per_cu")) {
-        if (value < 0 || value > 32) return SE_ERR_ARG;
-        g_max_blocks_per_cu.store(value); return SE_OK;
-    }
-    if (!std::strcmp(name, "coop_min_rows")) {
-        if (value < 0 || value > 65) return SE_ERR_ARG;
-        g_coop_min_rows.store(value); return SE_OK;
-    }
-    if (!std::strcmp(name, "nontemporal")) {
-        if (value < 0 || value > 3) return SE_ERR_ARG;
-        g_nontemporal.store(value); return SE_OK;
+    for (const Knob &k : kKnobs) {
+        if (std::strcmp(name, k.name)) continue;
+        if (value < k.lo || value > k.hi) return SE_ERR_ARG;
+        k.value->store(value);
+        return SE_OK;
     }
     return SE_ERR_ARG;
 }
@@ -315,13 +332,8 @@ int se_set_tuning(const char *name, int value)
 int se_get_tuning(const char *name)
 {
     if (!name) return SE_ERR_NULL;
-    if (!std::strcmp(name, "grid_blocks_per_cu")) return g_blocks_per_cu.load();
-    if (!std::strcmp(name, "group_major")) return g_group_major.load();
-    if (!std::strcmp(name, "nontemporal")) return g_nontemporal.load();
-    if (!std::strcmp(name, "block_threads")) return g_block_threads.load();
-    if (!std::strcmp(name, "tiles_per_block")) return g_tiles_per_block.load();
-    if (!std::strcmp(name, "max_blocks_per_cu")) return g_max_blocks_per_cu.load();
-    if (!std::strcmp(name, "coop_min_rows")) return g_coop_min_rows.load();
+    for (const Knob &k : kKnobs)
+        if (!std::strcmp(name, k.name)) return k.value->load();
     return SE_ERR_ARG;
 }
 
@@ -329,7 +341,7 @@ const char *se_strerror(int code)
 {
     switch (code) {
     case SE_OK: return "success";
-    case SE_ERR_ARG: return "invalid argument (n, group_size, iter or num_layers out of range)";
+    case SE_ERR_ARG: return "invalid argument (n, group_size, iter, layer range, flags or a size out of range)";
     case SE_ERR_DIVISIBILITY: return "n is not a multiple of group_size (only equal groups are defined)";
     case SE_ERR_NULL: return "a required pointer is NULL (momentum may be NULL only when mu == 0)";
     case SE_ERR_LAYOUT: return "bad layout (layer offsets not monotone from 0, buffers overlap or are misaligned)";

@@ -1,14 +1,16 @@
-// Cooperative form of the two steps for many rows per reduction (large groups, and the
-// Ring-SGD baseline where all n rows are reduced): the rows of one reduction are split over
-// the wavefronts of a workgroup, kRowsPerWave rows each, all wavefronts covering the same 64
+// Cooperative form of the step kernels for many rows per reduction (large groups, and the
+// Ring-SGD baseline where all n rows are reduced): the rows of one group are split over the
+// wavefronts of a workgroup, kRowsPerWave rows each, all wavefronts covering the same 64
 // lane-columns.  Every lane issues all loads of its rows at once (one round trip to HBM),
 // stages the values to be reduced in LDS, and after one barrier every wavefront walks the
 // staged rows in ascending worker id -- the documented summation order, so the result is
-// bit-identical to the single-wavefront kernel -- and finishes its own rows.
+// bit-identical to the single-wavefront form -- and finishes its own rows.
 //
-//   SESGD (Sec. 3.2, the SESGD update equation): stage x-hat, mean -> stored to own rows.
-//   Ring-SGD (Sec. 3.2, the DSGD equation): stage g, mean gradient -> momentum/SGD update of
-//   own rows (their x and v were loaded together with g).
+//   kSesgd   (Sec. 3.2, the SESGD update equation): stage x-hat; mean -> own rows.
+//   kGradAvg (Sec. 3.2, the DSGD equation applied per group; Ring-SGD when the group is all n
+//            workers): stage g; mean gradient -> momentum/SGD update of own rows, whose x and v
+//            were loaded together with g.
+//   kAvgOnly (Algorithm 1, last line): stage x; mean -> own rows.
 #include "se_device.hpp"
 
 #include <atomic>
@@ -17,7 +19,7 @@ namespace se {
 
 constexpr int kRowsPerWave = 4;
 
-template <int VEC, bool BF16, bool HAS_V, bool NTL, bool NTS, bool RING>
+template <int VEC, bool BF16, bool HAS_V, bool NT, int MODE>
 __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
 {
     extern __shared__ float staged[];          // [rows][64 lanes][VEC]
@@ -25,17 +27,12 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
     const int wave = (int)(threadIdx.x >> 6);
     const uint64_t gpitch_bytes = BF16 ? p.pitch_bytes / 2 : p.pitch_bytes;
 
+    const uint32_t grp = wave_group_of(p.seed, p.iter, p.n, p.m, lane);
     uint32_t g, tile;
-    uint64_t members;
-    if constexpr (RING) {
-        tile = blockIdx.x;
-        members = p.n >= 64 ? ~0ull : ((1ull << p.n) - 1ull);
-    } else {
-        const uint32_t grp = wave_group_of(p.seed, p.iter, p.n, p.m, lane);
-        if (p.group_major) { g = blockIdx.x / p.tiles; tile = blockIdx.x - g * p.tiles; }
-        else               { tile = blockIdx.x / (uint32_t)p.k; g = blockIdx.x - tile * (uint32_t)p.k; }
-        members = __ballot(grp == g);
-    }
+    if (p.group_major) { g = blockIdx.x / p.tiles; tile = blockIdx.x - g * p.tiles; }
+    else               { tile = blockIdx.x / (uint32_t)p.k; g = blockIdx.x - tile * (uint32_t)p.k; }
+    const uint64_t members = __ballot(grp == g);
+
     const uint32_t c = tile * 64u + (uint32_t)lane;
     const bool valid = c < p.nvec;
     const uint32_t off = c * (uint32_t)(VEC * 4);
@@ -58,27 +55,32 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
 #pragma unroll
         for (int r = 0; r < kRowsPerWave; ++r) {
             if (r < mine) {
-                X[r] = load_f32<VEC, NTL>((const char *)p.x + row[r] * p.pitch_bytes + off);
-                G[r] = load_grad<VEC, BF16, NTL>((const char *)p.g + row[r] * gpitch_bytes + goff);
-                if constexpr (HAS_V)
-                    V[r] = load_f32<VEC, NTL>((const char *)p.v + row[r] * p.pitch_bytes + off);
+                X[r] = load_f32<VEC, NT>((const char *)p.x + row[r] * p.pitch_bytes + off);
+                if constexpr (MODE != kAvgOnly) {
+                    G[r] = load_grad<VEC, BF16, NT>((const char *)p.g + row[r] * gpitch_bytes + goff);
+                    if constexpr (HAS_V)
+                        V[r] = load_f32<VEC, NT>((const char *)p.v + row[r] * p.pitch_bytes + off);
+                }
             }
         }
 #pragma unroll
         for (int r = 0; r < kRowsPerWave; ++r) {
             if (r < mine) {
                 Pack<VEC> out;
-                if constexpr (RING) {
+                if constexpr (MODE == kGradAvg) {
                     out = G[r];
+                } else if constexpr (MODE == kAvgOnly) {
+                    out = X[r];
                 } else {
                     Pack<VEC> vn;
 #pragma unroll
                     for (int q = 0; q < VEC; ++q) {
-                        vn.a[q] = HAS_V ? __builtin_fmaf(p.mu, V[r].a[q], G[r].a[q]) : G[r].a[q];
+                        const float d = decayed(p.wd, X[r].a[q], G[r].a[q]);
+                        vn.a[q] = HAS_V ? __builtin_fmaf(p.mu, V[r].a[q], d) : d;
                         out.a[q] = __builtin_fmaf(p.neg_lr, vn.a[q], X[r].a[q]);
                     }
                     if constexpr (HAS_V)
-                        store_f32<VEC, NTS>((char *)p.v + row[r] * p.pitch_bytes + off, vn);
+                        store_f32<VEC, NT>((char *)p.v + row[r] * p.pitch_bytes + off, vn);
                 }
                 store_f32<VEC, false>((char *)(staged + ((size_t)(first + r) * 64 + lane) * VEC), out);
             }
@@ -100,87 +102,80 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
 #pragma unroll
     for (int r = 0; r < kRowsPerWave; ++r) {
         if (r < mine) {
-            if constexpr (RING) {
+            if constexpr (MODE == kGradAvg) {
                 Pack<VEC> vn, xn;
 #pragma unroll
                 for (int q = 0; q < VEC; ++q) {
-                    vn.a[q] = HAS_V ? __builtin_fmaf(p.mu, V[r].a[q], mean.a[q]) : mean.a[q];
+                    const float d = decayed(p.wd, X[r].a[q], mean.a[q]);
+                    vn.a[q] = HAS_V ? __builtin_fmaf(p.mu, V[r].a[q], d) : d;
                     xn.a[q] = __builtin_fmaf(p.neg_lr, vn.a[q], X[r].a[q]);
                 }
                 if constexpr (HAS_V)
-                    store_f32<VEC, NTS>((char *)p.v + row[r] * p.pitch_bytes + off, vn);
-                store_f32<VEC, NTS>((char *)p.x + row[r] * p.pitch_bytes + off, xn);
+                    store_f32<VEC, NT>((char *)p.v + row[r] * p.pitch_bytes + off, vn);
+                store_f32<VEC, NT>((char *)p.x + row[r] * p.pitch_bytes + off, xn);
             } else {
-                store_f32<VEC, NTS>((char *)p.x + row[r] * p.pitch_bytes + off, mean);
+                store_f32<VEC, NT>((char *)p.x + row[r] * p.pitch_bytes + off, mean);
             }
         }
     }
 }
 
-template <int VEC, bool BF16, bool HAS_V, bool RING>
-static hipError_t launch_nt(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
+template <int VEC, bool BF16, bool HAS_V, bool NT, int MODE>
+static hipError_t launch_one(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
-    const int waves = (a.m + kRowsPerWave - 1) / kRowsPerWave;
-    dim3 grid(s.grid), block(waves * 64);
-    const size_t need = (size_t)a.m * 64 * VEC * sizeof(float);
+    const int waves = (a.m + kRowsPerWave - 1) / kRowsPerWave;     // <= 16 for m <= 64
+    const size_t need = (size_t)a.m * 64 * VEC * sizeof(float);    // <= 64 KiB
     const size_t lds = need > s.lds_bytes ? need : s.lds_bytes;
-#define SE_LAUNCH(NTL, NTS)                                                                     \
-    do {                                                                                        \
-        auto kern = se_coop_kernel<VEC, BF16, HAS_V, NTL, NTS, RING>;                           \
-        static std::atomic<bool> raised{false};                                                 \
-        if (!raised.load()) {                                                                   \
-            hipError_t e = hipFuncSetAttribute((const void *)kern,                              \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,      \
-                                               (int)kLdsPerCu);                                 \
-            if (e != hipSuccess) return e;                                                      \
-            raised.store(true);                                                                 \
-        }                                                                                       \
-        hipLaunchKernelGGL(kern, grid, block, lds, stream, a);                                  \
-    } while (0)
-    switch (s.nontemporal & 3) {
-    case 0: SE_LAUNCH(false, false); break;
-    case 1: SE_LAUNCH(true, false); break;
-    case 2: SE_LAUNCH(false, true); break;
-    default: SE_LAUNCH(true, true); break;
+    auto kern = se_coop_kernel<VEC, BF16, HAS_V, NT, MODE>;
+    static std::atomic<bool> raised{false};
+    if (!raised.load()) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
+        if (e != hipSuccess) return e;
+        raised.store(true);
     }
-#undef SE_LAUNCH
+    hipLaunchKernelGGL(kern, dim3(s.grid), dim3(waves * 64), lds, stream, a);
     return hipGetLastError();
 }
 
-template <int VEC, bool BF16, bool RING>
-static hipError_t launch_vec(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
+template <int VEC, bool BF16, bool NT>
+static hipError_t launch_mode(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
-    return a.v ? launch_nt<VEC, BF16, true, RING>(a, s, stream)
-               : launch_nt<VEC, BF16, false, RING>(a, s, stream);
+    const bool has_v = a.v != nullptr;
+    switch (a.mode) {
+    case kSesgd:
+        return has_v ? launch_one<VEC, BF16, true, NT, kSesgd>(a, s, stream)
+                     : launch_one<VEC, BF16, false, NT, kSesgd>(a, s, stream);
+    case kGradAvg:
+        return has_v ? launch_one<VEC, BF16, true, NT, kGradAvg>(a, s, stream)
+                     : launch_one<VEC, BF16, false, NT, kGradAvg>(a, s, stream);
+    default:
+        if constexpr (BF16) return hipErrorInvalidValue;
+        else return launch_one<VEC, false, false, NT, kAvgOnly>(a, s, stream);
+    }
 }
 
-template <bool RING>
-static hipError_t launch_any(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
+template <int VEC, bool BF16>
+static hipError_t launch_nt(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
+{
+    return s.nontemporal ? launch_mode<VEC, BF16, true>(a, s, stream)
+                         : launch_mode<VEC, BF16, false>(a, s, stream);
+}
+
+hipError_t launch_coop(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
     if (s.bf16) {
         switch (s.vec) {
-        case 4: return launch_vec<4, true, RING>(a, s, stream);
-        case 2: return launch_vec<2, true, RING>(a, s, stream);
-        default: return launch_vec<1, true, RING>(a, s, stream);
+        case 4: return launch_nt<4, true>(a, s, stream);
+        case 2: return launch_nt<2, true>(a, s, stream);
+        default: return launch_nt<1, true>(a, s, stream);
         }
     }
     switch (s.vec) {
-    case 4: return launch_vec<4, false, RING>(a, s, stream);
-    case 2: return launch_vec<2, false, RING>(a, s, stream);
-    default: return launch_vec<1, false, RING>(a, s, stream);
+    case 4: return launch_nt<4, false>(a, s, stream);
+    case 2: return launch_nt<2, false>(a, s, stream);
+    default: return launch_nt<1, false>(a, s, stream);
     }
-}
-
-// a.m rows are reduced together: the group size for SESGD, n for the ring baseline;
-// a.tiles counts tiles of 64 lane-columns; s.grid = tiles * (groups or 1).
-hipError_t launch_coop_step(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
-{
-    return launch_any<false>(a, s, stream);
-}
-
-hipError_t launch_coop_ring(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
-{
-    return launch_any<true>(a, s, stream);
 }
 
 }  // namespace se

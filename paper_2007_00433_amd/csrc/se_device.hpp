@@ -58,6 +58,20 @@ __device__ __forceinline__ uint32_t wave_group_of(uint64_t seed, int64_t iter, i
     return lane < n ? rank / (uint32_t)m : 0xFFFFFFFFu;
 }
 
+// Next member of a group: lowest set bit of the (wave-uniform) member mask, which is cleared.
+__device__ __forceinline__ uint64_t next_row(uint64_t &todo)
+{
+    const uint64_t r = (uint64_t)__builtin_ctzll(todo);
+    todo &= todo - 1;
+    return r;
+}
+
+// Decayed gradient d = wd*x + g as one fused operation; g itself when wd == 0.
+__device__ __forceinline__ float decayed(float wd, float x, float g)
+{
+    return wd != 0.0f ? __builtin_fmaf(wd, x, g) : g;
+}
+
 // ---------------------------------------------------------------- row accessors
 template <int N> struct Pack { float a[N]; };
 

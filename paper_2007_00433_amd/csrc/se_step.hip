@@ -1,65 +1,132 @@
-// Fused SESGD step (Sec. 3.2 "Gradient Correction", the SESGD update equation;
-// Algorithm 1 loop body): regroup, local SGD/momentum step into x-hat, mean of x-hat over
-// the group, write the mean to every member -- one pass over the packed buffer.
+// Single-wavefront form of the step kernels: one 64-lane workgroup per (group, tile of 64
+// lane-columns); a lane owns VEC consecutive columns of ALL member rows of its group, so the
+// values to reduce never leave registers and the group mean needs no cross-lane traffic.
+// A wavefront touches 64*VEC*4 contiguous bytes of each member row per access.
 //
-// Work decomposition: a workgroup handles one group g and a run of consecutive tiles of
-// BS lane-columns.  A lane owns VEC
-// consecutive columns of ALL member rows of its group, so x-hat never leaves registers and
-// the group mean needs no cross-lane traffic; a wavefront touches 64*VEC*4 contiguous
-// bytes of each member row per access.  The member list of group g is the bit mask
-// ballot(group_of(lane) == g): iterating its set bits visits the members in ascending
-// worker id, which is the summation order the library documents.  All of that is
-// wave-uniform, so row bases live in scalar registers and every row access is
-// (scalar base) + (one shared 32-bit lane offset).
+// The member list of group g is the bit mask ballot(group_of(lane) == g): iterating its set
+// bits visits the members in ascending worker id, which is the summation order the library
+// documents.  All of that is wave-uniform, so row bases live in scalar registers.
+//
+// Modes
+//   kSesgd   Sec. 3.2 "Gradient Correction", the SESGD update equation; Algorithm 1 loop body:
+//            local SGD/momentum step into x-hat, mean of x-hat over the group, mean written to
+//            every member.
+//   kGradAvg the uncorrected variant of Sec. 3.2 (the shuffle applied directly to the DSGD
+//            equation): mean of the gradients over the group, then every member updates on its
+//            own.  With one group of all n workers this is the Ring-SGD / DSGD step.
+//   kAvgOnly mean of the parameters over the group, nothing else (Algorithm 1, last line, when
+//            the group is all n workers).
 #include "se_device.hpp"
 
 #include <atomic>
 
 namespace se {
 
-template <int VEC, bool BF16, bool HAS_V, bool NTL, bool NTS, int B>
-__device__ __forceinline__ void member_batch(const StepArgs &p, uint64_t &todo, uint32_t off,
-                                             uint32_t goff, uint64_t gpitch_bytes,
-                                             Pack<VEC> &s, bool first)
+// ---- kSesgd: B members at once -------------------------------------------------------------
+template <int VEC, bool BF16, bool HAS_V, bool NT, int B>
+__device__ __forceinline__ void sesgd_batch(const StepArgs &p, uint64_t &todo, uint32_t off,
+                                            uint32_t goff, uint64_t gpitch_bytes,
+                                            Pack<VEC> &s, bool first)
 {
     uint64_t row[B];
 #pragma unroll
-    for (int b = 0; b < B; ++b) {
-        row[b] = (uint64_t)__builtin_ctzll(todo);
-        todo &= todo - 1;
-    }
+    for (int b = 0; b < B; ++b) row[b] = next_row(todo);
     Pack<VEC> X[B], G[B], V[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) {
-        X[b] = load_f32<VEC, NTL>((const char *)p.x + row[b] * p.pitch_bytes + off);
-        G[b] = load_grad<VEC, BF16, NTL>((const char *)p.g + row[b] * gpitch_bytes + goff);
+        X[b] = load_f32<VEC, NT>((const char *)p.x + row[b] * p.pitch_bytes + off);
+        G[b] = load_grad<VEC, BF16, NT>((const char *)p.g + row[b] * gpitch_bytes + goff);
         if constexpr (HAS_V)
-            V[b] = load_f32<VEC, NTL>((const char *)p.v + row[b] * p.pitch_bytes + off);
+            V[b] = load_f32<VEC, NT>((const char *)p.v + row[b] * p.pitch_bytes + off);
     }
 #pragma unroll
     for (int b = 0; b < B; ++b) {
         Pack<VEC> vn;
 #pragma unroll
         for (int c = 0; c < VEC; ++c) {
-            vn.a[c] = HAS_V ? __builtin_fmaf(p.mu, V[b].a[c], G[b].a[c]) : G[b].a[c];
+            const float d = decayed(p.wd, X[b].a[c], G[b].a[c]);
+            vn.a[c] = HAS_V ? __builtin_fmaf(p.mu, V[b].a[c], d) : d;
             const float xhat = __builtin_fmaf(p.neg_lr, vn.a[c], X[b].a[c]);
             s.a[c] = (first && b == 0) ? xhat : s.a[c] + xhat;
         }
         if constexpr (HAS_V)
-            store_f32<VEC, NTS>((char *)p.v + row[b] * p.pitch_bytes + off, vn);
+            store_f32<VEC, NT>((char *)p.v + row[b] * p.pitch_bytes + off, vn);
     }
 }
 
-template <int VEC, bool BF16, bool HAS_V, bool NTL, bool NTS, int BMAX, int BS>
-__global__ __launch_bounds__(BS) void se_step_kernel(const StepArgs p)
+// ---- kGradAvg / kAvgOnly, pass 1: sum one array over B members ---------------------------------
+template <int VEC, bool BF16, bool NT, bool PARAMS, int B>
+__device__ __forceinline__ void sum_batch(const StepArgs &p, uint64_t &todo, uint32_t off,
+                                          uint64_t pitch_bytes, Pack<VEC> &s, bool first)
 {
-    const int lane = (int)(threadIdx.x & 63u);
-    // Regrouping for this iteration, redone by every wavefront (a few hundred integer
-    // instructions, amortised over the tiles_per_block tiles the block walks through).
+    uint64_t row[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b) row[b] = next_row(todo);
+    Pack<VEC> A[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+        if constexpr (PARAMS) A[b] = load_f32<VEC, NT>((const char *)p.x + row[b] * pitch_bytes + off);
+        else A[b] = load_grad<VEC, BF16, NT>((const char *)p.g + row[b] * pitch_bytes + off);
+    }
+#pragma unroll
+    for (int b = 0; b < B; ++b)
+#pragma unroll
+        for (int c = 0; c < VEC; ++c)
+            s.a[c] = (first && b == 0) ? A[b].a[c] : s.a[c] + A[b].a[c];
+}
+
+// ---- kGradAvg, pass 2: every member updates with the group's mean gradient ---------------------
+template <int VEC, bool HAS_V, bool NT, int B>
+__device__ __forceinline__ void update_batch(const StepArgs &p, uint64_t &todo, uint32_t off,
+                                             const Pack<VEC> &gbar)
+{
+    uint64_t row[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b) row[b] = next_row(todo);
+    Pack<VEC> X[B], V[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+        X[b] = load_f32<VEC, NT>((const char *)p.x + row[b] * p.pitch_bytes + off);
+        if constexpr (HAS_V)
+            V[b] = load_f32<VEC, NT>((const char *)p.v + row[b] * p.pitch_bytes + off);
+    }
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+        Pack<VEC> vn, xn;
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            const float d = decayed(p.wd, X[b].a[c], gbar.a[c]);
+            vn.a[c] = HAS_V ? __builtin_fmaf(p.mu, V[b].a[c], d) : d;
+            xn.a[c] = __builtin_fmaf(p.neg_lr, vn.a[c], X[b].a[c]);
+        }
+        if constexpr (HAS_V)
+            store_f32<VEC, NT>((char *)p.v + row[b] * p.pitch_bytes + off, vn);
+        store_f32<VEC, NT>((char *)p.x + row[b] * p.pitch_bytes + off, xn);
+    }
+}
+
+// Applies CALL(B) to all m members in batches of BMAX, then 4, 2, 1 (wave-uniform control).
+#define SE_FOR_MEMBER_BATCHES(BMAX, m, CALL)                                               \
+    do {                                                                                   \
+        int rem_ = (m);                                                                    \
+        bool first = true;                                                                 \
+        while (rem_ >= BMAX) { CALL(BMAX); rem_ -= BMAX; first = false; }                  \
+        if constexpr (BMAX > 4) { if (rem_ >= 4) { CALL(4); rem_ -= 4; first = false; } }  \
+        if constexpr (BMAX > 2) { if (rem_ >= 2) { CALL(2); rem_ -= 2; first = false; } }  \
+        if constexpr (BMAX > 1) { if (rem_ >= 1) { CALL(1); } }                            \
+        (void)first;                                                                       \
+    } while (0)
+
+template <int VEC, bool BF16, bool HAS_V, bool NT, int MODE, int BMAX>
+__global__ __launch_bounds__(64) void se_step_kernel(const StepArgs p)
+{
+    const int lane = (int)threadIdx.x;
+    // Regrouping for this iteration, redone by every wavefront: a few hundred integer
+    // instructions next to ~20 KiB of memory traffic.
     const uint32_t grp = wave_group_of(p.seed, p.iter, p.n, p.m, lane);
     const uint64_t gpitch_bytes = BF16 ? p.pitch_bytes / 2 : p.pitch_bytes;
 
-    // block -> (group g, run of consecutive tiles)
+    // workgroup -> (group g, run of consecutive tiles)
     uint32_t g, chunk;
     if (p.group_major) { g = blockIdx.x / p.chunks; chunk = blockIdx.x - g * p.chunks; }
     else               { chunk = blockIdx.x / (uint32_t)p.k; g = blockIdx.x - chunk * (uint32_t)p.k; }
@@ -68,7 +135,7 @@ __global__ __launch_bounds__(BS) void se_step_kernel(const StepArgs p)
     const uint32_t tile1 = min(tile0 + p.tiles_per_block, p.tiles);
 
     for (uint32_t tile = tile0; tile < tile1; ++tile) {
-        const uint32_t c = tile * (uint32_t)BS + threadIdx.x;
+        const uint32_t c = tile * 64u + threadIdx.x;
         if (c >= p.nvec) break;
         const uint32_t off = c * (uint32_t)(VEC * 4);
         const uint32_t goff = BF16 ? off / 2 : off;
@@ -77,102 +144,92 @@ __global__ __launch_bounds__(BS) void se_step_kernel(const StepArgs p)
 #pragma unroll
         for (int q = 0; q < VEC; ++q) s.a[q] = 0.0f;
         uint64_t todo = members;
-        int rem = p.m;
-        bool first = true;
-        while (rem >= BMAX) {
-            member_batch<VEC, BF16, HAS_V, NTL, NTS, BMAX>(p, todo, off, goff, gpitch_bytes, s, first);
-            rem -= BMAX; first = false;
-        }
-        if constexpr (BMAX > 4) {
-            if (rem >= 4) {
-                member_batch<VEC, BF16, HAS_V, NTL, NTS, 4>(p, todo, off, goff, gpitch_bytes, s, first);
-                rem -= 4; first = false;
-            }
-        }
-        if constexpr (BMAX > 2) {
-            if (rem >= 2) {
-                member_batch<VEC, BF16, HAS_V, NTL, NTS, 2>(p, todo, off, goff, gpitch_bytes, s, first);
-                rem -= 2; first = false;
-            }
-        }
-        if constexpr (BMAX > 1) {
-            if (rem >= 1)
-                member_batch<VEC, BF16, HAS_V, NTL, NTS, 1>(p, todo, off, goff, gpitch_bytes, s, first);
+
+        if constexpr (MODE == kSesgd) {
+#define SE_CALL(B) sesgd_batch<VEC, BF16, HAS_V, NT, B>(p, todo, off, goff, gpitch_bytes, s, first)
+            SE_FOR_MEMBER_BATCHES(BMAX, p.m, SE_CALL);
+#undef SE_CALL
+        } else if constexpr (MODE == kGradAvg) {
+#define SE_CALL(B) sum_batch<VEC, BF16, NT, false, B>(p, todo, goff, gpitch_bytes, s, first)
+            SE_FOR_MEMBER_BATCHES(8, p.m, SE_CALL);
+#undef SE_CALL
+        } else {
+#define SE_CALL(B) sum_batch<VEC, false, NT, true, B>(p, todo, off, p.pitch_bytes, s, first)
+            SE_FOR_MEMBER_BATCHES(8, p.m, SE_CALL);
+#undef SE_CALL
         }
 
         Pack<VEC> mean;
 #pragma unroll
         for (int q = 0; q < VEC; ++q) mean.a[q] = s.a[q] * p.inv_m;
         todo = members;
-        while (todo) {
-            const uint64_t row = (uint64_t)__builtin_ctzll(todo);
-            todo &= todo - 1;
-            store_f32<VEC, NTS>((char *)p.x + row * p.pitch_bytes + off, mean);
+        if constexpr (MODE == kGradAvg) {
+#define SE_CALL(B) update_batch<VEC, HAS_V, NT, B>(p, todo, off, mean)
+            SE_FOR_MEMBER_BATCHES(4, p.m, SE_CALL);
+#undef SE_CALL
+        } else {
+            while (todo)
+                store_f32<VEC, NT>((char *)p.x + next_row(todo) * p.pitch_bytes + off, mean);
         }
     }
 }
 
-template <int VEC, bool BF16, bool HAS_V, int BMAX, int BS>
-static hipError_t launch_bs(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
+template <int VEC, bool BF16, bool HAS_V, bool NT, int MODE, int BMAX>
+static hipError_t launch_one(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
-    dim3 grid(s.grid), block(BS);
-    const size_t lds = s.lds_bytes;
-#define SE_LAUNCH(NTL, NTS)                                                                     \
-    do {                                                                                        \
-        auto kern = se_step_kernel<VEC, BF16, HAS_V, NTL, NTS, BMAX, BS>;                       \
-        static std::atomic<bool> raised{false};                                                 \
-        if (lds > 0 && !raised.load()) {                                                        \
-            hipError_t e = hipFuncSetAttribute((const void *)kern,                              \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,      \
-                                               (int)kLdsPerCu);                                 \
-            if (e != hipSuccess) return e;                                                      \
-            raised.store(true);                                                                 \
-        }                                                                                       \
-        hipLaunchKernelGGL(kern, grid, block, lds, stream, a);                                  \
-    } while (0)
-    switch (s.nontemporal & 3) {
-    case 0: SE_LAUNCH(false, false); break;
-    case 1: SE_LAUNCH(true, false); break;
-    case 2: SE_LAUNCH(false, true); break;
-    default: SE_LAUNCH(true, true); break;
+    auto kern = se_step_kernel<VEC, BF16, HAS_V, NT, MODE, BMAX>;
+    static std::atomic<bool> raised{false};
+    if (s.lds_bytes > 0 && !raised.load()) {
+        // the dynamic LDS is never touched: it only caps the resident workgroups per CU
+        hipError_t e = hipFuncSetAttribute((const void *)kern,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
+        if (e != hipSuccess) return e;
+        raised.store(true);
     }
-#undef SE_LAUNCH
+    hipLaunchKernelGGL(kern, dim3(s.grid), dim3(64), s.lds_bytes, stream, a);
     return hipGetLastError();
 }
 
-template <int VEC, bool BF16, bool HAS_V, int BMAX>
-static hipError_t launch_nt(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
+template <int VEC, bool BF16, bool NT>
+static hipError_t launch_mode(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
-    switch (s.block) {
-    case 64: return launch_bs<VEC, BF16, HAS_V, BMAX, 64>(a, s, stream);
-    case 128: return launch_bs<VEC, BF16, HAS_V, BMAX, 128>(a, s, stream);
-    default: return launch_bs<VEC, BF16, HAS_V, BMAX, 256>(a, s, stream);
+    const bool has_v = a.v != nullptr;
+    switch (a.mode) {
+    case kSesgd:
+        if (a.m >= 8)       // deeper batches keep more rows in flight for large groups
+            return has_v ? launch_one<VEC, BF16, true, NT, kSesgd, 8>(a, s, stream)
+                         : launch_one<VEC, BF16, false, NT, kSesgd, 8>(a, s, stream);
+        return has_v ? launch_one<VEC, BF16, true, NT, kSesgd, 4>(a, s, stream)
+                     : launch_one<VEC, BF16, false, NT, kSesgd, 4>(a, s, stream);
+    case kGradAvg:
+        return has_v ? launch_one<VEC, BF16, true, NT, kGradAvg, 8>(a, s, stream)
+                     : launch_one<VEC, BF16, false, NT, kGradAvg, 8>(a, s, stream);
+    default:
+        if constexpr (BF16) return hipErrorInvalidValue;
+        else return launch_one<VEC, false, false, NT, kAvgOnly, 8>(a, s, stream);
     }
 }
 
 template <int VEC, bool BF16>
-static hipError_t launch_vec(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
+static hipError_t launch_nt(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
-    const bool big = a.m >= 8;     // deeper batches keep more rows in flight for large groups
-    if (a.v) return big ? launch_nt<VEC, BF16, true, 8>(a, s, stream)
-                        : launch_nt<VEC, BF16, true, 4>(a, s, stream);
-    return big ? launch_nt<VEC, BF16, false, 8>(a, s, stream)
-               : launch_nt<VEC, BF16, false, 4>(a, s, stream);
+    return s.nontemporal ? launch_mode<VEC, BF16, true>(a, s, stream)
+                         : launch_mode<VEC, BF16, false>(a, s, stream);
 }
 
 hipError_t launch_step(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
     if (s.bf16) {
         switch (s.vec) {
-        case 4: return launch_vec<4, true>(a, s, stream);
-        case 2: return launch_vec<2, true>(a, s, stream);
-        default: return launch_vec<1, true>(a, s, stream);
+        case 4: return launch_nt<4, true>(a, s, stream);
+        case 2: return launch_nt<2, true>(a, s, stream);
+        default: return launch_nt<1, true>(a, s, stream);
         }
     }
     switch (s.vec) {
-    case 4: return launch_vec<4, false>(a, s, stream);
-    case 2: return launch_vec<2, false>(a, s, stream);
-    default: return launch_vec<1, false>(a, s, stream);
+    case 4: return launch_nt<4, false>(a, s, stream);
+    case 2: return launch_nt<2, false>(a, s, stream);
+    default: return launch_nt<1, false>(a, s, stream);
     }
 }
 

@@ -51,11 +51,10 @@ def test_seed_and_tuning_state():
     se.se_set_seed(12345678901234567890)
     assert se.se_get_seed() == 12345678901234567890
     se.se_set_seed(0)
-    assert len(se.TUNING_KNOBS) == 7
-    for name, good, bad in (("grid_blocks_per_cu", 8, -1), ("group_major", 1, 2),
-                            ("nontemporal", 3, 4), ("block_threads", 128, 96),
-                            ("tiles_per_block", 5, 0), ("max_blocks_per_cu", 2, 33),
-                            ("coop_min_rows", 4, 66)):
+    assert len(se.TUNING_KNOBS) == 5
+    for name, good, bad in (("group_major", 0, 2), ("nontemporal", 0, 2), ("tiles_per_block", 5, 0),
+                            ("max_blocks_per_cu", 2, 33), ("coop_min_rows", 4, 66)):
+        assert name in se.TUNING_KNOBS
         old = se.se_get_tuning(name)
         se.se_set_tuning(name, good)
         assert se.se_get_tuning(name) == good
@@ -130,3 +129,55 @@ def test_plan_rejects_bad_arguments_without_a_device():
     assert se.se_plan_raw(4, 2, 0, None, p) == se.SE_ERR_NULL
     assert se.se_plan_raw(128, 2, 0, p, p) == se.SE_ERR_UNSUPPORTED
     assert not out.any()                     # nothing written on error
+
+
+def test_extended_calls_reject_bad_arguments_without_a_device():
+    G, V = FAKE + (1 << 20), FAKE + (2 << 20)
+
+    def ex(first=0, last=2, flags=0, n=4, m=2, offs=OFFS, grads=G, bf16=0):
+        return se.se_step_ex_raw(FAKE, grads, bf16, V, offs, len(offs) - 1, first, last, n, m, 0,
+                                 0.1, 0.9, 0.0, flags, None)
+    assert ex(first=-1) == se.SE_ERR_ARG
+    assert ex(first=2, last=1) == se.SE_ERR_ARG
+    assert ex(last=3) == se.SE_ERR_ARG
+    assert ex(flags=2) == se.SE_ERR_ARG
+    assert ex(n=6, m=4) == se.SE_ERR_DIVISIBILITY
+    assert ex(grads=None) == se.SE_ERR_NULL
+    assert ex(grads=G + 2, bf16=0) == se.SE_ERR_LAYOUT
+    assert ex(first=1, last=1) == se.SE_OK            # empty layer range: nothing to launch
+    offs = np.asarray(OFFS, np.int64)
+    assert se.lib.se_global_average(None, offs.ctypes.data, 2, 4, None) == se.SE_ERR_NULL
+    assert se.lib.se_global_average(FAKE, offs.ctypes.data, 2, 0, None) == se.SE_ERR_ARG
+    assert se.lib.se_global_average(FAKE, offs.ctypes.data, 2, 65, None) == se.SE_ERR_UNSUPPORTED
+    assert se.lib.se_consensus(FAKE, offs.ctypes.data, 2, 4, None, None) == se.SE_ERR_NULL
+    assert se.lib.se_consensus(FAKE, offs.ctypes.data, 2, 4, FAKE + 100, None) == se.SE_ERR_LAYOUT
+    assert se.lib.se_consensus(FAKE, offs.ctypes.data, 2, 4, V + 4, None) == se.SE_ERR_LAYOUT
+    assert se.lib.se_consensus(None, offs.ctypes.data, 2, 4, V, None) == se.SE_ERR_NULL
+
+
+def test_comm_model_matches_the_oracle_and_the_paper():
+    """Host-only calculator (no device): Sec. 2.2 ring cost per layer, Sec. 2.3's 1500
+    handshakes for 50 layers on 16 workers, against the oracle's independent function."""
+    import oracle
+    from paper_2007_00433_amd import workloads as wl
+    fifty = list(range(0, 51 * 1000, 1000))
+    r = se.se_comm_model(fifty, 4, 16, 4, 125e6, 1e-4)
+    assert r["ring_handshakes"] == 1500 == oracle.handshakes(50, 16)
+    assert r["sesgd_handshakes"] == 300 == oracle.handshakes(50, 4)
+    w = wl.WORKLOADS["resnet50"]
+    offs = w.layer_offsets()
+    for lat in (1e-4, 5e-3):
+        r = se.se_comm_model(offs, 4, 16, 4, 125e6, lat)
+        ring = sum(oracle.ring_time(4.0 * s, 16, 125e6, lat) for s in w.sizes)
+        ses = sum(oracle.ring_time(4.0 * s, 4, 125e6, lat) for s in w.sizes)
+        assert abs(r["ring_seconds"] - ring) <= 1e-12 * ring
+        assert abs(r["sesgd_seconds"] - ses) <= 1e-12 * ses
+        assert r["sesgd_seconds"] < r["ring_seconds"]
+    offs_arr = np.asarray(offs, np.int64)
+    assert se.lib.se_comm_model(offs_arr.ctypes.data, len(offs) - 1, 4, 16, 3, 1e9, 0.0,
+                                None, None, None, None) == se.SE_ERR_DIVISIBILITY
+    assert se.lib.se_comm_model(offs_arr.ctypes.data, len(offs) - 1, 4, 16, 4, 0.0, 0.0,
+                                None, None, None, None) == se.SE_ERR_ARG
+    assert se.lib.se_comm_model(None, 1, 4, 16, 4, 1e9, 0.0, None, None, None, None) == se.SE_ERR_NULL
+    assert se.lib.se_comm_model(offs_arr.ctypes.data, len(offs) - 1, 4, 16, 4, 1e9, 0.0,
+                                None, None, None, None) == se.SE_OK

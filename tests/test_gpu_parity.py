@@ -307,11 +307,10 @@ def test_special_values_propagate():
 def test_results_do_not_depend_on_launch_knobs_or_stream():
     ref = None
     stream = torch.cuda.Stream()
-    shapes = [dict(), dict(block_threads=256, max_blocks_per_cu=0, group_major=0, nontemporal=0),
-              dict(block_threads=128, tiles_per_block=3, max_blocks_per_cu=4, nontemporal=1),
-              dict(block_threads=64, tiles_per_block=7, max_blocks_per_cu=1, group_major=0, nontemporal=2),
-              dict(block_threads=256, tiles_per_block=1000, grid_blocks_per_cu=2),
-              dict(block_threads=64, max_blocks_per_cu=32, grid_blocks_per_cu=16),
+    shapes = [dict(), dict(max_blocks_per_cu=0, group_major=0, nontemporal=0),
+              dict(tiles_per_block=3, max_blocks_per_cu=4),
+              dict(tiles_per_block=7, max_blocks_per_cu=1, group_major=0),
+              dict(tiles_per_block=1000, max_blocks_per_cu=32),
               dict(coop_min_rows=0), dict(coop_min_rows=1), dict(coop_min_rows=2, max_blocks_per_cu=3),
               dict(coop_min_rows=16, nontemporal=0, group_major=0)]
     defaults = {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}
@@ -447,3 +446,145 @@ def test_full_size_bert_base_sampled():
 
 def test_full_size_bert_base_full_group_sampled():
     _full_size_sampled("bert_base_full", 2)
+
+
+# ------------------------------------------------------------------------ extended calls
+GA = se.SE_FLAG_GRAD_AVG
+
+
+@pytest.mark.parametrize("coop", [0, 1, 8])
+def test_step_ex_weight_decay_and_gradient_averaging(coop):
+    se.se_set_tuning("coop_min_rows", coop)
+    for n, m, ncols, dtype, wd, flags in [(16, 4, 1029, "f32", 5e-4, 0), (16, 4, 1029, "f32", 1e-4, GA),
+                                          (64, 8, 770, "bf16", 5e-4, 0), (64, 16, 514, "bf16", 0.0, GA),
+                                          (12, 3, 63, "f32", 5e-4, GA), (8, 8, 260, "f32", 1e-4, GA),
+                                          (6, 1, 129, "f32", 5e-4, GA), (9, 9, 5, "bf16", 5e-4, 0)]:
+        for use_v in (True, False):
+            case = Case(n, ncols, dtype=dtype, use_v=use_v, distinct_rows=True, v_std=0.01 if use_v else 0.0)
+            offs = case.offsets()
+            for t in range(3):
+                hg = case.grads(t, 1e-2)
+                se.se_step_ex(case.dx, case.dg, case.dv, offs, n, m, t, 0.1, 0.9 if use_v else 0.0, wd, flags,
+                              grads_are_bf16=(dtype == "bf16"))
+                oracle.step_ex(case.hx, hg, case.hv, m, t, 0.1, 0.9 if use_v else 0.0, wd, flags)
+            case.check(f"ex coop={coop} n={n} m={m} cols={ncols} {dtype} wd={wd} flags={flags} v={use_v}")
+
+
+def test_step_ex_layer_ranges_with_misaligned_boundaries():
+    """Stepping layer ranges one at a time (boundaries at arbitrary columns, so ranges start
+    and end off the 128-bit grid) equals one full step; untouched layers stay untouched."""
+    sizes = [5, 1, 250, 3, 1021, 64, 2, 777, 130]
+    n, m, P = 16, 4, sum(sizes)
+    for dtype in ("f32", "bf16"):
+        full, parts = Case(n, P, dtype=dtype, distinct_rows=True, v_std=0.01), Case(n, P, dtype=dtype, distinct_rows=True, v_std=0.01)
+        offs = full.offsets(sizes)
+        L = len(sizes)
+        for t in range(2):
+            hg = full.grads(t, 1e-2)
+            parts.dg = full.dg
+            se.se_step_ex(full.dx, full.dg, full.dv, offs, n, m, t, 0.1, 0.9, 5e-4, 0, grads_are_bf16=(dtype == "bf16"))
+            oracle.step_ex(full.hx, hg, full.hv, m, t, 0.1, 0.9, 5e-4, 0)
+            for first, last in [(L - 2, L), (0, 1), (1, 4), (4, 5), (5, 5), (5, L - 2)]:   # back to front, like backward
+                se.se_step_ex(parts.dx, parts.dg, parts.dv, offs, n, m, t, 0.1, 0.9, 5e-4, 0,
+                              first_layer=first, last_layer=last, grads_are_bf16=(dtype == "bf16"))
+        full.check("layer ranges: full step")
+        torch.cuda.synchronize()
+        assert torch.equal(full.dx, parts.dx) and torch.equal(full.dv, parts.dv)
+    # a single middle range leaves the other columns alone
+    case = Case(n, P, distinct_rows=True, v_std=0.01)
+    hg = case.grads(0, 1e-2)
+    se.se_step_ex(case.dx, case.dg, case.dv, offs, n, m, 0, 0.1, 0.9, 0.0, GA, first_layer=2, last_layer=5)
+    oracle.step_ex(case.hx, hg, case.hv, m, 0, 0.1, 0.9, 0.0, GA, cols=(offs[2], offs[5]))
+    case.check("middle range only")
+
+
+def test_local_sesgd_schedule():
+    """Local-SESGD (Sec. 4.1 baselines): synchronise every second iteration only; the
+    iterations in between are calls with group_size = 1."""
+    n, m, P = 16, 4, 3000
+    case = Case(n, P)
+    offs = case.offsets()
+    for t in range(6):
+        hg = case.grads(t, 1e-2)
+        mm = m if t % 2 == 1 else 1
+        se.se_step(case.dx, case.dg, case.dv, offs, n, mm, t, 0.1, 0.9)
+        oracle.step(case.hx, hg, case.hv, mm, t, 0.1, 0.9)
+    case.check("local sesgd")
+
+
+@pytest.mark.parametrize("coop", [0, 1])
+def test_global_average(coop):
+    se.se_set_tuning("coop_min_rows", coop)
+    for n, ncols, shift in [(16, 1027, 0), (64, 300, 0), (7, 64, 1), (1, 10, 0), (33, 2, 2)]:
+        case = Case(n, ncols, use_v=False, distinct_rows=True, shift=shift)
+        se.se_global_average(case.dx, case.offsets(), n)
+        oracle.global_average(case.hx)
+        case.check(f"global average n={n} cols={ncols}")
+
+
+def test_consensus_diagnostics():
+    out = torch.full((2,), 7.0, dtype=torch.float64, device="cuda")
+    for n, ncols in [(16, 100003), (64, 777), (3, 1), (1, 50)]:
+        case = Case(n, ncols, use_v=False, distinct_rows=True)
+        offs = case.offsets()
+        se.se_consensus(case.dx, offs, n, out)
+        torch.cuda.synchronize()
+        d, s = oracle.consensus(case.hx)
+        got = out.cpu().numpy()
+        assert abs(got[0] - d) <= 1e-10 * max(abs(d), 1e-300), (n, ncols, got, d)
+        assert abs(got[1] - s) <= 1e-10 * np.abs(case.hx.astype(np.float64)).sum()
+        se.se_global_average(case.dx, offs, n)
+        se.se_consensus(case.dx, offs, n, out)
+        torch.cuda.synchronize()
+        assert out[0].item() == 0.0                    # identical replicas: exactly zero
+
+
+def test_divergence_without_correction_on_the_gpu():
+    """The paper's point (Sec. 3.2), on the device: averaging gradients per group lets the
+    replicas drift apart, averaging parameters does not."""
+    n, m, P = 16, 4, 50000
+    naive, corrected = Case(n, P, use_v=False), Case(n, P, use_v=False)
+    offs = naive.offsets()
+    out = torch.zeros(2, dtype=torch.float64, device="cuda")
+    dist = {}
+    for T in (20, 80):
+        for t in range(0 if T == 20 else 20, T):
+            naive.grads(t, 1e-2)
+            se.se_step_ex(naive.dx, naive.dg, None, offs, n, m, t, 0.1, 0.0, 0.0, GA)
+            se.se_step_ex(corrected.dx, naive.dg, None, offs, n, m, t, 0.1, 0.0, 0.0, 0)
+        se.se_consensus(naive.dx, offs, n, out); torch.cuda.synchronize(); dn = out[0].item()
+        se.se_consensus(corrected.dx, offs, n, out); torch.cuda.synchronize(); dc = out[0].item()
+        dist[T] = (dn, dc)
+    assert dist[80][0] > 3.0 * dist[20][0]
+    assert dist[80][1] < 1.5 * dist[20][1]
+    assert dist[80][1] < dist[80][0] / 10
+
+
+def test_full_size_resnet50_gradient_averaging_and_decay_sampled():
+    """Headline shape through se_step_ex: weight decay 1e-4 (the paper's ResNet-50 setting)
+    with the corrected update, then one uncorrected step; sampled columns against the oracle."""
+    w = wl.WORKLOADS["resnet50"]
+    n, m, P = w.n, w.group_size, w.P
+    pitch = se.se_pitch(P)
+    offs = w.layer_offsets(pitch)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(77)
+    x = torch.zeros(n, pitch, device="cuda"); x[:, :P] = torch.randn(P, device="cuda", generator=gen) * 0.05
+    v = torch.zeros(n, pitch, device="cuda")
+    g = torch.zeros(n, pitch, device="cuda")
+    cols = torch.from_numpy(wl.sample_columns(pitch, 20000, seed=2)).cuda()
+    hx, hv = x[:, cols].cpu().numpy().copy(), v[:, cols].cpu().numpy().copy()
+    for t, flags in enumerate([0, 0, GA]):
+        g[:, :P] = torch.randn(n, P, device="cuda", generator=gen) * 1e-3
+        hg = g[:, cols].cpu().numpy().copy()
+        se.se_step_ex(x, g, v, offs, n, m, t, 0.1, 0.9, 1e-4, flags)
+        oracle.step_ex(hx, hg, hv, m, t, 0.1, 0.9, 1e-4, flags)
+    torch.cuda.synchronize()
+    assert bit_mismatches(x[:, cols].cpu().numpy(), hx) == 0
+    assert bit_mismatches(v[:, cols].cpu().numpy(), hv) == 0
+    out = torch.zeros(2, dtype=torch.float64, device="cuda")
+    se.se_global_average(x, offs, n)
+    se.se_consensus(x, offs, n, out)
+    torch.cuda.synchronize()
+    oracle.global_average(hx)
+    assert bit_mismatches(x[:, cols].cpu().numpy(), hx) == 0
+    assert out[0].item() == 0.0
