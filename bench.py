@@ -160,7 +160,7 @@ def main():
         with open(prof) as f:
             pj = json.load(f)
         if pj.get("pitch") == pitch:
-            traffic = pj["kernels"].get("se_step_kernel", {}).get("traffic_bytes")
+            traffic = pj["kernels"].get("sesgd", {}).get("traffic_bytes")
 
     out = {
         "metric": "SESGD steps/sec and achieved HBM GB/s (% of peak), n=16 ResNet-50-shaped"
@@ -176,9 +176,8 @@ def main():
                    "group_size": m, "tensors": len(w.sizes), "params_per_worker": P,
                    "pitch": pitch, "lr": w.lr, "momentum": w.mu, "grad_dtype": w.grad_dtype,
                    "grad_buffers_cycled": len(pool),
-                   "tuning": {k: se.se_get_tuning(k) for k in
-                              ("grid_blocks_per_cu", "group_major", "nontemporal")}},
-        "roofline": {"bound": "hbm", "kernel": "se_step_kernel", "achieved": round(achieved, 1),
+                   "tuning": {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}},
+        "roofline": {"bound": "hbm", "kernel": "se_step_kernel" if m < se.se_get_tuning("coop_min_rows") or se.se_get_tuning("coop_min_rows") == 0 else "se_coop_kernel", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "bytes_per_launch": bytes_per_launch,
                      "avg_launch_ms": round(per_launch * 1e3, 5)},

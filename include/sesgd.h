@@ -184,8 +184,6 @@ int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
  *   "max_blocks_per_cu"   cap on resident workgroups per compute unit, enforced by requesting
  *                         160 KiB / cap of (unused) LDS per workgroup; 0 = no cap (default 8)
  *   "tiles_per_block"     consecutive 64-lane tiles one workgroup walks through (default 1)
- *   "group_major"         block order. 1 (default): all tiles of group 0, then group 1, ...;
- *                         0: the groups of one tile side by side
  *   "nontemporal"         1 (default): streaming (non-temporal) loads and stores; 0: plain
  *   "coop_min_rows"       number of rows reduced together (group_size; n for se_ring_step and
  *                         se_global_average) from which the rows are split over the wavefronts

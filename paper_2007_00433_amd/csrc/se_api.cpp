@@ -13,7 +13,6 @@
 namespace {
 
 std::atomic<uint64_t> g_seed{0};
-std::atomic<int> g_group_major{1};
 std::atomic<int> g_nontemporal{1};
 std::atomic<int> g_tiles_per_block{1};
 std::atomic<int> g_max_blocks_per_cu{8};  // resident workgroups per CU (0 = no cap)
@@ -92,7 +91,6 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     a.n = j.n; a.m = j.m; a.k = j.n / j.m;
     a.neg_lr = -j.lr; a.mu = j.mu; a.inv_m = 1.0f / (float)j.m; a.wd = j.wd;
     a.mode = j.mode;
-    a.group_major = g_group_major.load();
 
     se::LaunchShape s;
     s.vec = vec;
@@ -101,11 +99,7 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     const int cap = g_max_blocks_per_cu.load();
     s.lds_bytes = cap > 0 ? (se::kLdsPerCu / (uint32_t)cap) & ~1023u : 0u;
     const int coop = g_coop_min_rows.load();
-    if (coop > 0 && j.m >= coop) {
-        s.grid = a.tiles * (uint32_t)a.k;              // < 2^24 * 64
-        return se::launch_coop(a, s, j.stream);
-    }
-    s.grid = a.chunks * (uint32_t)a.k;
+    if (coop > 0 && j.m >= coop) return se::launch_coop(a, s, j.stream);
     return se::launch_step(a, s, j.stream);
 }
 
@@ -163,7 +157,6 @@ struct Knob { const char *name; std::atomic<int> *value; int lo, hi; };
 Knob kKnobs[] = {
     {"max_blocks_per_cu", &g_max_blocks_per_cu, 0, 32},
     {"tiles_per_block", &g_tiles_per_block, 1, 65536},
-    {"group_major", &g_group_major, 0, 1},
     {"nontemporal", &g_nontemporal, 0, 1},
     {"coop_min_rows", &g_coop_min_rows, 0, 65},
 };

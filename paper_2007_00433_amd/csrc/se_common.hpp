@@ -30,21 +30,19 @@ struct StepArgs {
     int n, m, k;               // workers, rows reduced together, groups
     float neg_lr, mu, inv_m, wd;
     int mode;                  // Mode
-    int group_major;           // block order: 1 = all chunks of a group, then the next group
 };
 
 struct LaunchShape {
     int vec;                // 4, 2 or 1 columns per lane
     bool bf16;              // gradient storage
     bool nontemporal;       // streaming loads and stores
-    uint32_t grid;          // workgroups
     uint32_t lds_bytes;     // dynamic LDS requested only to cap resident workgroups per CU
 };
 
-// single-wavefront form: s.grid = a.chunks * a.k
+// single-wavefront form: grid (a.chunks, a.k)
 hipError_t launch_step(const StepArgs &a, const LaunchShape &s, hipStream_t stream);
 // cooperative form: a.m rows reduced together by ceil(a.m / 4) wavefronts per workgroup,
-// s.grid = a.tiles * a.k
+// grid (a.tiles, a.k)
 hipError_t launch_coop(const StepArgs &a, const LaunchShape &s, hipStream_t stream);
 hipError_t launch_plan(uint64_t seed, int64_t iter, int n, int m, int32_t *group_of_dev,
                        int32_t *members_dev, hipStream_t stream);

@@ -27,11 +27,8 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
     const int wave = (int)(threadIdx.x >> 6);
     const uint64_t gpitch_bytes = BF16 ? p.pitch_bytes / 2 : p.pitch_bytes;
 
-    const uint32_t grp = wave_group_of(p.seed, p.iter, p.n, p.m, lane);
-    uint32_t g, tile;
-    if (p.group_major) { g = blockIdx.x / p.tiles; tile = blockIdx.x - g * p.tiles; }
-    else               { tile = blockIdx.x / (uint32_t)p.k; g = blockIdx.x - tile * (uint32_t)p.k; }
-    const uint64_t members = __ballot(grp == g);
+    const uint32_t g = blockIdx.y, tile = blockIdx.x;
+    const uint64_t members = wave_members(p.seed, p.iter, p.n, p.m, g, lane);
 
     const uint32_t c = tile * 64u + (uint32_t)lane;
     const bool valid = c < p.nvec;
@@ -134,7 +131,7 @@ static hipError_t launch_one(const StepArgs &a, const LaunchShape &s, hipStream_
         if (e != hipSuccess) return e;
         raised.store(true);
     }
-    hipLaunchKernelGGL(kern, dim3(s.grid), dim3(waves * 64), lds, stream, a);
+    hipLaunchKernelGGL(kern, dim3(a.tiles, (uint32_t)a.k), dim3(waves * 64), lds, stream, a);
     return hipGetLastError();
 }
 

@@ -38,14 +38,24 @@ __device__ __forceinline__ uint32_t worker_key(uint64_t seed, int64_t iter, int 
     return absorb(h, (uint32_t)i);
 }
 
-// Rank of this lane's worker among workers 0..n-1, n <= 64.  Lanes >= n return garbage.
+// Rank of this lane's worker among workers 0..n-1, n <= 64: the number of workers whose
+// (key, id) pair is lexicographically smaller, counted with one 64-bit compare per worker.
+// Lanes >= n take the largest key, so they never count as smaller (the loop runs over n
+// rounded up to 4) and their own result is garbage.
 __device__ __forceinline__ uint32_t wave_rank(uint64_t seed, int64_t iter, int n, int lane)
 {
-    const uint32_t key = worker_key(seed, iter, n, lane);
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    const uint32_t key = lane < n ? worker_key(seed, iter, n, lane) : 0xFFFFFFFFu;
+    const u32x2 mine2 = {(uint32_t)lane, key};                     // low word: id, high word: key
+    const uint64_t mine = __builtin_bit_cast(uint64_t, mine2);
     uint32_t rank = 0;
-    for (int j = 0; j < n; ++j) {
-        const uint32_t kj = (uint32_t)__builtin_amdgcn_readlane((int)key, j);
-        rank += (kj < key || (kj == key && j < lane)) ? 1u : 0u;
+    for (int j = 0; j < n; j += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const u32x2 other2 = {(uint32_t)(j + u),
+                                  (uint32_t)__builtin_amdgcn_readlane((int)key, j + u)};
+            rank += __builtin_bit_cast(uint64_t, other2) < mine ? 1u : 0u;
+        }
     }
     return rank;
 }
@@ -56,6 +66,15 @@ __device__ __forceinline__ uint32_t wave_group_of(uint64_t seed, int64_t iter, i
 {
     const uint32_t rank = wave_rank(seed, iter, n, lane);
     return lane < n ? rank / (uint32_t)m : 0xFFFFFFFFu;
+}
+
+// Members of group g as a lane mask (bit i = worker i), wave-uniform: the workers whose rank
+// falls in [g*m, (g+1)*m).  Exactly m bits are set.
+__device__ __forceinline__ uint64_t wave_members(uint64_t seed, int64_t iter, int n, int m,
+                                                 uint32_t g, int lane)
+{
+    const uint32_t rank = wave_rank(seed, iter, n, lane);
+    return __ballot(lane < n && rank - g * (uint32_t)m < (uint32_t)m);
 }
 
 // Next member of a group: lowest set bit of the (wave-uniform) member mask, which is cleared.

@@ -121,16 +121,13 @@ template <int VEC, bool BF16, bool HAS_V, bool NT, int MODE, int BMAX>
 __global__ __launch_bounds__(64) void se_step_kernel(const StepArgs p)
 {
     const int lane = (int)threadIdx.x;
-    // Regrouping for this iteration, redone by every wavefront: a few hundred integer
-    // instructions next to ~20 KiB of memory traffic.
-    const uint32_t grp = wave_group_of(p.seed, p.iter, p.n, p.m, lane);
     const uint64_t gpitch_bytes = BF16 ? p.pitch_bytes / 2 : p.pitch_bytes;
-
-    // workgroup -> (group g, run of consecutive tiles)
-    uint32_t g, chunk;
-    if (p.group_major) { g = blockIdx.x / p.chunks; chunk = blockIdx.x - g * p.chunks; }
-    else               { chunk = blockIdx.x / (uint32_t)p.k; g = blockIdx.x - chunk * (uint32_t)p.k; }
-    const uint64_t members = __ballot(grp == g);           // wave-uniform, m bits set
+    // workgroup -> (group g = blockIdx.y, run of consecutive tiles = blockIdx.x): all tiles of
+    // group 0 are dispatched first, then group 1, ...
+    const uint32_t g = blockIdx.y, chunk = blockIdx.x;
+    // Regrouping for this iteration, redone by every wavefront: ~150 instructions next to
+    // ~20 KiB of memory traffic.
+    const uint64_t members = wave_members(p.seed, p.iter, p.n, p.m, g, lane);
     const uint32_t tile0 = chunk * p.tiles_per_block;
     const uint32_t tile1 = min(tile0 + p.tiles_per_block, p.tiles);
 
@@ -186,7 +183,7 @@ static hipError_t launch_one(const StepArgs &a, const LaunchShape &s, hipStream_
         if (e != hipSuccess) return e;
         raised.store(true);
     }
-    hipLaunchKernelGGL(kern, dim3(s.grid), dim3(64), s.lds_bytes, stream, a);
+    hipLaunchKernelGGL(kern, dim3(a.chunks, (uint32_t)a.k), dim3(64), s.lds_bytes, stream, a);
     return hipGetLastError();
 }
 

@@ -20,9 +20,17 @@ import sys
 
 
 def kernel_key(name: str) -> str:
-    for key in ("se_step_kernel", "se_ring_kernel", "se_calib_copy_kernel", "se_plan_kernel"):
+    """Classifies a kernel name.  The step kernels carry their mode as a template argument:
+    se_step_kernel<VEC, BF16, HAS_V, NT, MODE, BMAX> and se_coop_kernel<VEC, BF16, HAS_V, NT, MODE>
+    with MODE 0 = SESGD update, 1 = gradient averaging (the ring baseline), 2 = average only."""
+    for key in ("se_calib_copy_kernel", "se_plan_kernel", "se_consensus_kernel"):
         if key in name:
             return key
+    for key in ("se_step_kernel", "se_coop_kernel"):
+        if key in name and "<" in name:
+            args = [a.strip() for a in name[name.index("<") + 1:name.index(">")].split(",")]
+            mode = {"0": "sesgd", "1": "ring", "2": "avgonly"}.get(args[4], args[4])
+            return f"{mode}"
     return ""
 
 
@@ -69,15 +77,17 @@ def main():
              f"    rocprofv3 --pmc WRITE_SIZE -d OUT/write -o write --output-format csv -- python3 R/bench.py --skip-cpu-baseline --steps 6 --warmup 2 --workload {workload}",
              f"    python -m paper_2007_00433_amd.profile_summary OUT {workload} profiles/{os.path.basename(stem)}", "",
              "## Kernel durations (--kernel-trace --stats)", "",
-             "| kernel | calls | avg ns | min ns | max ns | algorithmic bytes | GB/s at avg | % of 8 TB/s |",
-             "|---|---|---|---|---|---|---|---|"]
-    for k in ("se_step_kernel", "se_ring_kernel", "se_calib_copy_kernel"):
+             "Rows: `sesgd` = se_step (SESGD update), `ring` = se_ring_step (gradient averaging over all n).",
+             "",
+             "| what | kernel | calls | avg ns | min ns | max ns | algorithmic bytes | GB/s at avg | % of 8 TB/s |",
+             "|---|---|---|---|---|---|---|---|---|"]
+    for k in ("sesgd", "ring", "se_calib_copy_kernel"):
         if k not in stats:
             continue
         s = stats[k]
         alg = 2 * copy_bytes if k == "se_calib_copy_kernel" else rd + wr
         gbs = alg / s["avg_ns"]
-        lines.append(f"| `{s['name'][:70]}` | {s['calls']} | {s['avg_ns']:.0f} | {s['min_ns']:.0f} | "
+        lines.append(f"| {k} | `{s['name'][:62]}` | {s['calls']} | {s['avg_ns']:.0f} | {s['min_ns']:.0f} | "
                      f"{s['max_ns']:.0f} | {alg} | {gbs:.1f} | {gbs / 80.0:.1f} |")
         out["kernels"][k] = {"avg_ns": s["avg_ns"], "calls": s["calls"], "algorithmic_bytes": alg,
                              "gbs": gbs}
@@ -88,7 +98,7 @@ def main():
               f"{w_scale:.5f} KiB per count.", "",
               "| kernel | FETCH_SIZE avg | WRITE_SIZE avg | read bytes | written bytes | traffic bytes | algorithmic bytes | traffic / algorithmic |",
               "|---|---|---|---|---|---|---|---|"]
-    for k in ("se_step_kernel", "se_ring_kernel"):
+    for k in ("sesgd", "ring"):
         if k not in fetch or k not in write:
             continue
         rb = fetch[k][0] * f_scale * 1024.0

@@ -307,12 +307,12 @@ def test_special_values_propagate():
 def test_results_do_not_depend_on_launch_knobs_or_stream():
     ref = None
     stream = torch.cuda.Stream()
-    shapes = [dict(), dict(max_blocks_per_cu=0, group_major=0, nontemporal=0),
+    shapes = [dict(), dict(max_blocks_per_cu=0, nontemporal=0),
               dict(tiles_per_block=3, max_blocks_per_cu=4),
-              dict(tiles_per_block=7, max_blocks_per_cu=1, group_major=0),
+              dict(tiles_per_block=7, max_blocks_per_cu=1),
               dict(tiles_per_block=1000, max_blocks_per_cu=32),
               dict(coop_min_rows=0), dict(coop_min_rows=1), dict(coop_min_rows=2, max_blocks_per_cu=3),
-              dict(coop_min_rows=16, nontemporal=0, group_major=0)]
+              dict(coop_min_rows=16, nontemporal=0)]
     defaults = {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}
     for q, shape in enumerate(shapes):
         for k, val in {**defaults, **shape}.items():
