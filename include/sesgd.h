@@ -189,6 +189,9 @@ int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
  *                         se_global_average) from which the rows are split over the wavefronts
  *                         of a workgroup and the values to reduce are staged in LDS; below it
  *                         one wavefront owns all rows of its group.  0 = never (default 8)
+ *   "cache_resident_mib"  a launch that moves fewer MiB than this (default 192; the Infinity
+ *                         Cache holds 256 MiB) uses plain accesses and no residency cap, which
+ *                         is faster when nothing streams from HBM; 0 = always stream
  * Returns SE_ERR_ARG for an unknown name or a value out of range. */
 int se_set_tuning(const char *name, int value);
 int se_get_tuning(const char *name);

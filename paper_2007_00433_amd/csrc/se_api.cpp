@@ -17,6 +17,7 @@ std::atomic<int> g_nontemporal{1};
 std::atomic<int> g_tiles_per_block{1};
 std::atomic<int> g_max_blocks_per_cu{8};  // resident workgroups per CU (0 = no cap)
 std::atomic<int> g_coop_min_rows{8};      // rows reduced together from which the LDS form is used (0 = never)
+std::atomic<int> g_cache_resident_mib{192};  // launches moving fewer MiB stay in the 256 MiB Infinity Cache
 
 thread_local char t_last_error[256] = "";
 
@@ -95,8 +96,13 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     se::LaunchShape s;
     s.vec = vec;
     s.bf16 = j.grad_bytes == 2;
-    s.nontemporal = g_nontemporal.load() != 0;
-    const int cap = g_max_blocks_per_cu.load();
+    // Streaming accesses and a residency cap pay off when the launch streams from HBM; a launch
+    // whose whole traffic fits the Infinity Cache is faster with plain accesses and no cap.
+    const uint64_t per_elem = 8u + (uint64_t)j.grad_bytes + (j.v ? 8u : 0u);
+    const uint64_t moved = (uint64_t)j.n * (uint64_t)(c1 - c0) * per_elem;
+    const bool streams = moved >= ((uint64_t)g_cache_resident_mib.load() << 20);
+    s.nontemporal = streams && g_nontemporal.load() != 0;
+    const int cap = streams ? g_max_blocks_per_cu.load() : 0;
     s.lds_bytes = cap > 0 ? (se::kLdsPerCu / (uint32_t)cap) & ~1023u : 0u;
     const int coop = g_coop_min_rows.load();
     if (coop > 0 && j.m >= coop) return se::launch_coop(a, s, j.stream);
@@ -159,6 +165,7 @@ Knob kKnobs[] = {
     {"tiles_per_block", &g_tiles_per_block, 1, 65536},
     {"nontemporal", &g_nontemporal, 0, 1},
     {"coop_min_rows", &g_coop_min_rows, 0, 65},
+    {"cache_resident_mib", &g_cache_resident_mib, 0, 1 << 20},
 };
 
 }  // namespace

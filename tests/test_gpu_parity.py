@@ -312,7 +312,8 @@ def test_results_do_not_depend_on_launch_knobs_or_stream():
               dict(tiles_per_block=7, max_blocks_per_cu=1),
               dict(tiles_per_block=1000, max_blocks_per_cu=32),
               dict(coop_min_rows=0), dict(coop_min_rows=1), dict(coop_min_rows=2, max_blocks_per_cu=3),
-              dict(coop_min_rows=16, nontemporal=0)]
+              dict(coop_min_rows=16, nontemporal=0),
+              dict(cache_resident_mib=0), dict(cache_resident_mib=0, coop_min_rows=1, max_blocks_per_cu=2)]
     defaults = {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}
     for q, shape in enumerate(shapes):
         for k, val in {**defaults, **shape}.items():
@@ -354,6 +355,39 @@ def test_both_kernel_forms_for_every_group_size(coop):
         case = Case(n, ncols, dtype=dtype, use_v=(n % 2 == 0), v_std=0.0)
         run_ring(case, 2, 0.1, 0.9 if n % 2 == 0 else 0.0, 1e-2)
         case.check(f"coop={coop} ring n={n} cols={ncols} {dtype}")
+
+
+def test_steps_captured_in_a_graph_replay_correctly():
+    """Ten se_step launches (a different iteration and gradient buffer each) captured in one
+    HIP graph; every replay must continue the trajectory exactly as eager launches do.  The
+    library records only kernel nodes (no memset, no allocation)."""
+    n, m, P, K = 16, 4, 6000, 10
+    eager, graphed = Case(n, P), Case(n, P)
+    offs = eager.offsets()
+    grads = [torch.from_numpy(wl.host_grads(n, P, 1e-2, 0, t)).cuda() for t in range(K)]
+    side = torch.cuda.Stream()
+    # warm every kernel variant outside the capture (first launches set a function attribute)
+    warm = Case(n, P)
+    se.se_step(warm.dx, grads[0], warm.dv, offs, n, m, 0, 0.1, 0.9, side)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for t in range(K):
+            se.se_step(graphed.dx, grads[t], graphed.dv, offs, n, m, t, 0.1, 0.9,
+                       torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for replay in range(3):
+        graph.replay()
+        for t in range(K):
+            se.se_step(eager.dx, grads[t], eager.dv, offs, n, m, t, 0.1, 0.9)
+        torch.cuda.synchronize()
+        assert torch.equal(eager.dx, graphed.dx) and torch.equal(eager.dv, graphed.dv), replay
+        # unrelated eager work between replays
+        (eager.dx * 1.0).sum().item()
+    for _ in range(3):
+        for t in range(K):
+            oracle.step(eager.hx, grads[t].cpu().numpy(), eager.hv, m, t, 0.1, 0.9)
+    eager.check("graph replays vs oracle")
 
 
 def test_resume_from_any_iteration():
