@@ -1,0 +1,120 @@
+// Host-only harness for the C ABI: se_api.cpp is linked against mock launchers that never
+// touch a device but check, for every launch the API would make, that the argument block is
+// consistent with what the kernels assume (alignment of every row at the first column, column
+// count, tile and grid arithmetic), and record which columns each launch covers.  main() then
+// drives the entry points with fake addresses of every alignment class and with layer ranges
+// at arbitrary boundaries, and verifies that the launches tile the requested columns exactly
+// once.  Built with -fsanitize=address,undefined by tests/test_host_sanitizers.py.
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "../../paper_2007_00433_amd/csrc/se_common.hpp"
+#include "../../include/sesgd.h"
+
+namespace {
+
+struct Rec { uintptr_t x, g, v; uint64_t cols; int vec; bool coop, bf16; int mode, m, k; uint32_t tiles; };
+std::vector<Rec> g_recs;
+int g_failures = 0;
+
+#define EXPECT(cond)                                                                          \
+    do { if (!(cond)) { std::printf("FAIL %s:%d: %s\n", __FILE__, __LINE__, #cond); ++g_failures; } } while (0)
+
+hipError_t record(const se::StepArgs &a, const se::LaunchShape &s, bool coop)
+{
+    const uintptr_t fa = (uintptr_t)s.vec * 4u, ga = (uintptr_t)s.vec * (s.bf16 ? 2u : 4u);
+    EXPECT(s.vec == 1 || s.vec == 2 || s.vec == 4);
+    EXPECT((uintptr_t)a.x % fa == 0);
+    EXPECT(a.pitch_bytes % fa == 0);
+    if (a.v) EXPECT((uintptr_t)a.v % fa == 0);
+    if (a.mode != se::kAvgOnly) { EXPECT(a.g != nullptr); EXPECT((uintptr_t)a.g % ga == 0); }
+    EXPECT(a.nvec > 0);
+    EXPECT((uint64_t)a.nvec * (uint64_t)s.vec * 4u <= a.pitch_bytes);      // stays inside a row
+    EXPECT(a.tiles == (a.nvec + 63u) / 64u);
+    EXPECT(a.m >= 1 && a.m <= a.n && a.n <= se::kMaxWorkers && a.k * a.m == a.n);
+    EXPECT(a.inv_m == 1.0f / (float)a.m);
+    EXPECT(s.lds_bytes <= se::kLdsPerCu);
+    if (coop) {
+        EXPECT((size_t)a.m * 64 * s.vec * 4 <= 64u * 1024u);               // staging fits
+        EXPECT((a.m + 3) / 4 <= 16);                                       // <= 1024 threads
+    } else {
+        EXPECT(a.tiles_per_block >= 1);
+        EXPECT(a.chunks == (a.tiles + a.tiles_per_block - 1) / a.tiles_per_block);
+    }
+    g_recs.push_back({(uintptr_t)a.x, (uintptr_t)a.g, (uintptr_t)a.v, (uint64_t)a.nvec * (uint64_t)s.vec,
+                      s.vec, coop, s.bf16, a.mode, a.m, a.k, a.tiles});
+    return hipSuccess;
+}
+
+}  // namespace
+
+namespace se {
+hipError_t launch_step(const StepArgs &a, const LaunchShape &s, hipStream_t) { return record(a, s, false); }
+hipError_t launch_coop(const StepArgs &a, const LaunchShape &s, hipStream_t) { return record(a, s, true); }
+hipError_t launch_plan(uint64_t, int64_t, int, int, int32_t *, int32_t *, hipStream_t) { return hipSuccess; }
+hipError_t launch_consensus(const float *, uint64_t, uint64_t, int, double *, hipStream_t) { return hipSuccess; }
+hipError_t launch_calib_copy(void *, const void *, uint64_t, hipStream_t) { return hipSuccess; }
+}  // namespace se
+
+// The launches recorded since `from` must cover columns [c0, c1) of the row that starts at
+// `base`, in order, without gap or overlap.
+static void expect_exact_cover(size_t from, uintptr_t base, int64_t c0, int64_t c1)
+{
+    uintptr_t next = base + (uintptr_t)c0 * 4u;
+    for (size_t i = from; i < g_recs.size(); ++i) {
+        EXPECT(g_recs[i].x == next);
+        next += g_recs[i].cols * 4u;
+    }
+    EXPECT(next == base + (uintptr_t)c1 * 4u);
+}
+
+int main()
+{
+    const uintptr_t X = 0x100000000ull, G = 0x200000000ull, V = 0x300000000ull;
+    int calls = 0;
+    for (int sx = 0; sx < 4; ++sx) for (int sg = 0; sg < 4; ++sg) for (int sv = 0; sv < 4; ++sv)
+    for (int bf16 = 0; bf16 < 2; ++bf16) for (int64_t pitch : {1, 2, 3, 4, 5, 63, 64, 66, 257, 4096, 4099}) {
+        int64_t offs[4] = {0, pitch / 3, pitch / 3 + (pitch > 7 ? 5 : 0), pitch};
+        float *x = (float *)(X + 4u * sx);
+        void *g = (void *)(G + (bf16 ? 2u : 4u) * sg);
+        float *v = (float *)(V + 4u * sv);
+        for (int first = 0; first <= 3; ++first) for (int last = first; last <= 3; ++last) {
+            for (int n : {1, 4, 16, 64}) for (int m : {1, 4, 16, 64}) {
+                if (m > n) continue;
+                const size_t from = g_recs.size();
+                const int rc = se_step_ex(x, g, bf16, (n & 4) ? v : nullptr, offs, 3, first, last, n, m, 7,
+                                          0.1f, (n & 4) ? 0.9f : 0.0f, 1e-4f, (m & 4) ? SE_FLAG_GRAD_AVG : 0u, nullptr);
+                EXPECT(rc == SE_OK);
+                expect_exact_cover(from, (uintptr_t)x, offs[first], offs[last]);
+                ++calls;
+            }
+        }
+        const size_t from = g_recs.size();
+        EXPECT(se_global_average(x, offs, 3, 16, nullptr) == SE_OK);
+        expect_exact_cover(from, (uintptr_t)x, 0, pitch);
+        EXPECT(se_ring_step(x, (const float *)(G + 4u * sg), v, offs, 3, 16, 0.1f, 0.9f, nullptr) == SE_OK);
+    }
+    // the aligned, padded case is a single 128-bit launch
+    {
+        int64_t offs[2] = {0, 25557056};
+        const size_t from = g_recs.size();
+        EXPECT(se_step((float *)X, (const float *)G, (float *)V, offs, 1, 16, 4, 0, 0.1f, 0.9f, nullptr) == SE_OK);
+        EXPECT(g_recs.size() == from + 1 && g_recs[from].vec == 4 && !g_recs[from].coop &&
+               g_recs[from].tiles == 25557056u / 4 / 64);
+        EXPECT(se_ring_step((float *)X, (const float *)G, (float *)V, offs, 1, 16, 0.1f, 0.9f, nullptr) == SE_OK);
+        EXPECT(g_recs.back().coop && g_recs.back().mode == se::kGradAvg && g_recs.back().m == 16 && g_recs.back().k == 1);
+    }
+    // error paths write nothing and launch nothing
+    {
+        int64_t offs[2] = {0, 100};
+        const size_t from = g_recs.size();
+        EXPECT(se_step((float *)X, (const float *)G, nullptr, offs, 1, 6, 4, 0, 0.1f, 0.0f, nullptr) == SE_ERR_DIVISIBILITY);
+        EXPECT(se_step((float *)X, (const float *)X, nullptr, offs, 1, 4, 2, 0, 0.1f, 0.0f, nullptr) == SE_ERR_LAYOUT);
+        EXPECT(se_step_ex((float *)X, (const void *)G, 0, nullptr, offs, 1, 0, 2, 4, 2, 0, 0.1f, 0.0f, 0.0f, 0u, nullptr) == SE_ERR_ARG);
+        EXPECT(g_recs.size() == from);
+    }
+    std::printf("%d calls, %zu launches checked, %d failures\n", calls, g_recs.size(), g_failures);
+    return g_failures ? 1 : 0;
+}
