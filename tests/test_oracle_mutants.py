@@ -6,6 +6,7 @@ import subprocess
 import pytest
 
 import oracle
+import test_oracle_ext as ext_pins
 import test_oracle_plan as plan_pins
 import test_oracle_step as step_pins
 
@@ -29,6 +30,22 @@ MUTANTS = {
     "ring mean not scaled": ("gbar = s * inv_n;", "gbar = s;"),
     "ring counts worker 0 twice": ("for (i = 1; i < n; ++i)\n            s = s +", "for (i = 0; i < n; ++i)\n            s = s +"),
     "ring update sign": ("params[idx] = fmaf(-lr, vn, params[idx]);", "params[idx] = fmaf(lr, vn, params[idx]);"),
+    # --- the extended functions
+    "decay sign (corrected form)": ("float d = (wd != 0.0f) ? fmaf(wd, params[idx], gg) : gg;",
+                                    "float d = (wd != 0.0f) ? fmaf(-wd, params[idx], gg) : gg;"),
+    "decay applied to the gradient, not the parameter": ("float d = (wd != 0.0f) ? fmaf(wd, params[idx], gg) : gg;",
+                                                         "float d = (wd != 0.0f) ? fmaf(wd, gg, gg) : gg;"),
+    "decay dropped in the gradient-averaging form": ("float d = (wd != 0.0f) ? fmaf(wd, params[idx], gbar) : gbar;",
+                                                     "float d = gbar;"),
+    "gradient mean not scaled": ("gbar = s * inv_m;\n                for (r = 0; r < m; ++r) {", "gbar = s;\n                for (r = 0; r < m; ++r) {"),
+    "gradient-averaging form averages parameters too": ("                    params[idx] = fmaf(-lr, vn, params[idx]);\n                }\n            } else {",
+                                                        "                    params[idx] = fmaf(-lr, vn, params[(int64_t)mem[0] * pitch + e]);\n                }\n            } else {"),
+    "global average skips the last worker": ("for (i = 1; i < n; ++i)\n            s = s + params[(int64_t)i * pitch + e];",
+                                             "for (i = 1; i < n - 1; ++i)\n            s = s + params[(int64_t)i * pitch + e];"),
+    "consensus uses the sum as the mean": ("mean = s / (double)n;", "mean = s;"),
+    "consensus forgets the square": ("d += t * t;", "d += t;"),
+    "ring time drops the latency term": ("(layer_bytes / ((double)workers * nu) + t_tau)", "(layer_bytes / ((double)workers * nu))"),
+    "handshakes count one direction only": ("return (long)layers * 2L * (long)(workers - 1);", "return (long)layers * (long)(workers - 1);"),
 }
 
 
@@ -48,6 +65,13 @@ def battery(golden_dir):
         ("partition n=4", lambda: plan_pins.test_partition_brute_force_small_n(4)),
         ("keys", plan_pins.test_keys_match_independent_python_implementation),
         ("seed/iter dependence", plan_pins.test_same_seed_same_plan_and_seed_matters),
+        ("ex = basic", ext_pins.test_general_step_reduces_to_the_basic_step),
+        ("grad-avg = ring", ext_pins.test_gradient_averaging_over_all_workers_is_ring_sgd),
+        ("ex brute n=4", lambda: ext_pins.test_general_step_against_exact_rational_brute_force(4)),
+        ("decay = torch", ext_pins.test_weight_decay_is_the_library_optimizer_convention),
+        ("global average", ext_pins.test_global_average_pins),
+        ("consensus", ext_pins.test_consensus_closed_forms),
+        ("cost model", ext_pins.test_cost_model_numbers_of_the_paper),
     ]
     failed = []
     for name, fn in checks:
