@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace se {
 
 constexpr int kMaxWorkers = 64;              // one lane per worker in the plan generator
@@ -49,5 +51,20 @@ hipError_t launch_plan(uint64_t seed, int64_t iter, int n, int m, int32_t *group
 hipError_t launch_consensus(const float *x, uint64_t pitch_elems, uint64_t ncols, int n,
                             double *out_dev, hipStream_t stream);
 hipError_t launch_calib_copy(void *dst, const void *src, uint64_t nbytes, hipStream_t stream);
+
+// Lets `kernel` request up to the whole LDS of a compute unit as dynamic shared memory; done
+// once per device (bit per device ordinal in `done`).
+inline hipError_t allow_full_lds(const void *kernel, std::atomic<uint64_t> &done)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load() & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
+    if (e != hipSuccess) return e;
+    done.fetch_or(bit);
+    return hipSuccess;
+}
 
 }  // namespace se

@@ -124,13 +124,9 @@ static hipError_t launch_one(const StepArgs &a, const LaunchShape &s, hipStream_
     const size_t need = (size_t)a.m * 64 * VEC * sizeof(float);    // <= 64 KiB
     const size_t lds = need > s.lds_bytes ? need : s.lds_bytes;
     auto kern = se_coop_kernel<VEC, BF16, HAS_V, NT, MODE>;
-    static std::atomic<bool> raised{false};
-    if (!raised.load()) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
-        if (e != hipSuccess) return e;
-        raised.store(true);
-    }
+    static std::atomic<uint64_t> allowed{0};
+    const hipError_t e = allow_full_lds((const void *)kern, allowed);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(a.tiles, (uint32_t)a.k), dim3(waves * 64), lds, stream, a);
     return hipGetLastError();
 }

@@ -175,13 +175,11 @@ template <int VEC, bool BF16, bool HAS_V, bool NT, int MODE, int BMAX>
 static hipError_t launch_one(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
     auto kern = se_step_kernel<VEC, BF16, HAS_V, NT, MODE, BMAX>;
-    static std::atomic<bool> raised{false};
-    if (s.lds_bytes > 0 && !raised.load()) {
+    static std::atomic<uint64_t> allowed{0};
+    if (s.lds_bytes > 0) {
         // the dynamic LDS is never touched: it only caps the resident workgroups per CU
-        hipError_t e = hipFuncSetAttribute((const void *)kern,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
+        const hipError_t e = allow_full_lds((const void *)kern, allowed);
         if (e != hipSuccess) return e;
-        raised.store(true);
     }
     hipLaunchKernelGGL(kern, dim3(a.chunks, (uint32_t)a.k), dim3(64), s.lds_bytes, stream, a);
     return hipGetLastError();
