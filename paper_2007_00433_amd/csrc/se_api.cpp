@@ -15,7 +15,7 @@ namespace {
 std::atomic<uint64_t> g_seed{0};
 std::atomic<int> g_nontemporal{1};
 std::atomic<int> g_tiles_per_block{1};
-std::atomic<int> g_max_blocks_per_cu{8};  // resident workgroups per CU (0 = no cap)
+std::atomic<int> g_max_blocks_per_cu{7};  // resident workgroups per CU (0 = no cap)
 std::atomic<int> g_coop_min_rows{8};      // rows reduced together from which the LDS form is used (0 = never)
 std::atomic<int> g_cache_resident_mib{192};  // launches moving fewer MiB stay in the 256 MiB Infinity Cache
 
