@@ -622,3 +622,40 @@ def test_full_size_resnet50_gradient_averaging_and_decay_sampled():
     oracle.global_average(hx)
     assert bit_mismatches(x[:, cols].cpu().numpy(), hx) == 0
     assert out[0].item() == 0.0
+
+
+def test_maximum_row_length_sampled():
+    """Rows of 2^30 - 64 elements, the longest the library accepts (byte offsets inside a row
+    reach 2^32 - 256): sampled columns, including the last tile, against the oracle, through
+    the 128-bit path and through the scalar path (base shifted by one element)."""
+    pitch = (1 << 30) - 64
+    n, m = 2, 2
+    offs = [0, pitch]
+    assert se.se_step_raw("se_step", 0x100000, 0x100000 + (1 << 40), None, [0, 1 << 30], 1, n, m, 0,
+                          0.1, 0.0, None) == se.SE_ERR_UNSUPPORTED
+    gen = torch.Generator(device="cuda"); gen.manual_seed(5)
+    cols_np = wl.sample_columns(pitch, 6000, seed=3)
+    cols = torch.from_numpy(cols_np).cuda()
+    for shift in (0, 1):
+        say(f"max row length, shift {shift}")
+        xb = torch.empty(n * pitch + 4, device="cuda"); vb = torch.empty(n * pitch + 4, device="cuda")
+        gb = torch.empty(n * pitch + 4, device="cuda")
+        x, v, g = (b[shift:shift + n * pitch].view(n, pitch) for b in (xb, vb, gb))
+        for i in range(n):
+            x[i].normal_(0, 0.05, generator=gen); v[i].normal_(0, 0.01, generator=gen)
+        hx, hv = x[:, cols].cpu().numpy().copy(), v[:, cols].cpu().numpy().copy()
+        for t in range(2):
+            for i in range(n):
+                g[i].normal_(0, 1e-2, generator=gen)
+            hg = g[:, cols].cpu().numpy().copy()
+            se.se_step(x, g, v, offs, n, m, t, 0.1, 0.9)
+            torch.cuda.synchronize()
+            assert torch.equal(x[0], x[1])                  # one group of both workers
+            se.se_ring_step(x, g, v, offs, n, 0.1, 0.9)
+            oracle.step(hx, hg, hv, m, t, 0.1, 0.9)
+            oracle.ring_step(hx, hg, hv, 0.1, 0.9)
+        torch.cuda.synchronize()
+        assert bit_mismatches(x[:, cols].cpu().numpy(), hx) == 0
+        assert bit_mismatches(v[:, cols].cpu().numpy(), hv) == 0
+        del x, v, g, xb, vb, gb
+        torch.cuda.empty_cache()
