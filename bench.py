@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--skip-copy", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=3.0, help="target CPU time per oracle leg")
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE")
+    ap.add_argument("--all-workloads", action="store_true",
+                    help="also time se_step / se_ring_step / the oracle on every configured workload "
+                         "(reported under 'all_workloads'; the headline fields are unchanged)")
     return ap.parse_args()
 
 
@@ -101,6 +104,44 @@ def cpu_baseline(w, pitch, target_seconds):
         "single_thread_sample": f"first {cols1} columns, 2 steps, 1 thread",
         "gbytes_per_s": round(n * pitch * (16 + w.grad_bytes) / multi / 1e9, 2),
     }
+
+
+def measure_workload(name, steps, warmup, cpu_seconds, torch, se, wl):
+    """steps/s and effective GB/s of se_step and se_ring_step on one workload, plus the oracle."""
+    w = wl.WORKLOADS[name]
+    n, m, P = w.n, w.group_size, w.P
+    pitch = se.se_pitch(P)
+    offs = w.layer_offsets(pitch)
+    bf16 = w.grad_dtype == "bf16"
+    step_fn = se.se_step_bf16g if bf16 else se.se_step
+    ring_fn = se.se_ring_step_bf16g if bf16 else se.se_ring_step
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1)
+    x = torch.zeros(n, pitch, device="cuda")
+    x[:, :P] = torch.randn(P, device="cuda", generator=gen) * w.param_std
+    v = torch.zeros(n, pitch, device="cuda")
+    pool = []
+    for _ in range(2):
+        g = torch.zeros(n, pitch, device="cuda", dtype=torch.bfloat16 if bf16 else torch.float32)
+        for i in range(n):
+            g[i, :P] = (torch.randn(P, device="cuda", generator=gen) * w.grad_std).to(g.dtype)
+        pool.append(g)
+    mu = w.mu if w.mu else 0.9          # the tiny config has mu = 0: time it with a momentum buffer anyway
+    nbytes = se.se_step_bytes(pitch, n, w.grad_bytes, True)
+    k = max(steps, 20) if nbytes < 1e9 else max(5, steps // 5) if nbytes > 2e10 else steps
+    _, per = timed_steps(lambda t, s: step_fn(x, pool[t % 2], v, offs, n, m, t, w.lr, mu, s), k, warmup, torch)
+    _, rper = timed_steps(lambda t, s: ring_fn(x, pool[t % 2], v, offs, n, w.lr, mu, s), k, warmup, torch)
+    res = {"n": n, "group_size": m, "params_per_worker": P, "pitch": pitch, "grad_dtype": w.grad_dtype,
+           "bytes_per_step": nbytes, "steps_timed": k,
+           "se_step": {"steps_per_s": round(1.0 / per, 2), "gbs": round(nbytes / per / 1e9, 1),
+                       "frac_of_peak": round(nbytes / per / 1e9 / HBM_PEAK_GBS, 4)},
+           "se_ring_step": {"steps_per_s": round(1.0 / rper, 2), "gbs": round(nbytes / rper / 1e9, 1),
+                            "frac_of_peak": round(nbytes / rper / 1e9 / HBM_PEAK_GBS, 4)}}
+    del x, v, pool
+    torch.cuda.empty_cache()
+    if cpu_seconds > 0:
+        res["cpu_baseline"] = cpu_baseline(w, pitch, cpu_seconds)
+    return res
 
 
 def main():
@@ -215,6 +256,11 @@ def main():
         del pool, x, v
         torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(w, pitch, args.cpu_seconds)
+    if args.all_workloads:
+        out["all_workloads"] = {}
+        for name in ("tiny", "resnet20", "resnet50", "vgg16", "bert_base", "bert_base_full"):
+            out["all_workloads"][name] = measure_workload(
+                name, args.steps, args.warmup, 0.0 if args.skip_cpu_baseline else 1.0, torch, se, wl)
     print(json.dumps(out), flush=True)
 
 
