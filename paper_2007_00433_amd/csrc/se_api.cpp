@@ -14,8 +14,7 @@ namespace {
 
 std::atomic<uint64_t> g_seed{0};
 std::atomic<int> g_nontemporal{1};
-std::atomic<int> g_tiles_per_block{1};
-std::atomic<int> g_max_blocks_per_cu{7};  // resident workgroups per CU (0 = no cap)
+std::atomic<int> g_max_blocks_per_cu{6};  // resident workgroups per CU (0 = no cap)
 std::atomic<int> g_coop_min_rows{8};      // rows reduced together from which the LDS form is used (0 = never)
 std::atomic<int> g_cache_resident_mib{192};  // launches moving fewer MiB stay in the 256 MiB Infinity Cache
 
@@ -87,8 +86,6 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     a.pitch_bytes = (uint64_t)j.pitch * 4u;
     a.nvec = (uint32_t)((c1 - c0) / vec);
     a.tiles = (a.nvec + 63u) / 64u;
-    a.tiles_per_block = (uint32_t)g_tiles_per_block.load();
-    a.chunks = (a.tiles + a.tiles_per_block - 1) / a.tiles_per_block;
     a.n = j.n; a.m = j.m; a.k = j.n / j.m;
     a.neg_lr = -j.lr; a.mu = j.mu; a.inv_m = 1.0f / (float)j.m; a.wd = j.wd;
     a.mode = j.mode;
@@ -165,7 +162,6 @@ int plan_check(int n, int group_size, int64_t iter, const void *group_of)
 struct Knob { const char *name; std::atomic<int> *value; int lo, hi; };
 Knob kKnobs[] = {
     {"max_blocks_per_cu", &g_max_blocks_per_cu, 0, 32},
-    {"tiles_per_block", &g_tiles_per_block, 1, 65536},
     {"nontemporal", &g_nontemporal, 0, 1},
     {"coop_min_rows", &g_coop_min_rows, 0, 65},
     {"cache_resident_mib", &g_cache_resident_mib, 0, 1 << 20},

@@ -27,8 +27,6 @@ struct StepArgs {
     uint64_t pitch_bytes;      // row distance of x and v in bytes (half of it for bf16 g)
     uint32_t nvec;
     uint32_t tiles;
-    uint32_t tiles_per_block;  // single-wavefront form: consecutive tiles per workgroup
-    uint32_t chunks;           // ceil(tiles / tiles_per_block): workgroups per group
     int n, m, k;               // workers, rows reduced together, groups
     float neg_lr, mu, inv_m, wd;
     int mode;                  // Mode
@@ -41,7 +39,7 @@ struct LaunchShape {
     uint32_t lds_bytes;     // dynamic LDS requested only to cap resident workgroups per CU
 };
 
-// single-wavefront form: grid (a.chunks, a.k)
+// single-wavefront form: grid (a.tiles, a.k)
 hipError_t launch_step(const StepArgs &a, const LaunchShape &s, hipStream_t stream);
 // cooperative form: a.m rows reduced together by ceil(a.m / 4) wavefronts per workgroup,
 // grid (a.tiles, a.k)

@@ -19,7 +19,7 @@ namespace se {
 
 constexpr int kRowsPerWave = 4;
 
-template <int VEC, bool BF16, bool HAS_V, bool NT, int MODE>
+template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, bool NT, int MODE>
 __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
 {
     extern __shared__ float staged[];          // [rows][64 lanes][VEC]
@@ -72,7 +72,7 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
                     Pack<VEC> vn;
 #pragma unroll
                     for (int q = 0; q < VEC; ++q) {
-                        const float d = decayed(p.wd, X[r].a[q], G[r].a[q]);
+                        const float d = HAS_WD ? __builtin_fmaf(p.wd, X[r].a[q], G[r].a[q]) : G[r].a[q];
                         vn.a[q] = HAS_V ? __builtin_fmaf(p.mu, V[r].a[q], d) : d;
                         out.a[q] = __builtin_fmaf(p.neg_lr, vn.a[q], X[r].a[q]);
                     }
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
                 Pack<VEC> vn, xn;
 #pragma unroll
                 for (int q = 0; q < VEC; ++q) {
-                    const float d = decayed(p.wd, X[r].a[q], mean.a[q]);
+                    const float d = HAS_WD ? __builtin_fmaf(p.wd, X[r].a[q], mean.a[q]) : mean.a[q];
                     vn.a[q] = HAS_V ? __builtin_fmaf(p.mu, V[r].a[q], d) : d;
                     xn.a[q] = __builtin_fmaf(p.neg_lr, vn.a[q], X[r].a[q]);
                 }
@@ -117,13 +117,13 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
     }
 }
 
-template <int VEC, bool BF16, bool HAS_V, bool NT, int MODE>
+template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, bool NT, int MODE>
 static hipError_t launch_one(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
     const int waves = (a.m + kRowsPerWave - 1) / kRowsPerWave;     // <= 16 for m <= 64
     const size_t need = (size_t)a.m * 64 * VEC * sizeof(float);    // <= 64 KiB
     const size_t lds = need > s.lds_bytes ? need : s.lds_bytes;
-    auto kern = se_coop_kernel<VEC, BF16, HAS_V, NT, MODE>;
+    auto kern = se_coop_kernel<VEC, BF16, HAS_V, HAS_WD, NT, MODE>;
     static std::atomic<uint64_t> allowed{0};
     const hipError_t e = allow_full_lds((const void *)kern, allowed);
     if (e != hipSuccess) return e;
@@ -131,20 +131,25 @@ static hipError_t launch_one(const StepArgs &a, const LaunchShape &s, hipStream_
     return hipGetLastError();
 }
 
+template <int VEC, bool BF16, bool NT, int MODE>
+static hipError_t launch_flags(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
+{
+    const bool has_v = a.v != nullptr, has_wd = a.wd != 0.0f;
+    if (has_v) return has_wd ? launch_one<VEC, BF16, true, true, NT, MODE>(a, s, stream)
+                             : launch_one<VEC, BF16, true, false, NT, MODE>(a, s, stream);
+    return has_wd ? launch_one<VEC, BF16, false, true, NT, MODE>(a, s, stream)
+                  : launch_one<VEC, BF16, false, false, NT, MODE>(a, s, stream);
+}
+
 template <int VEC, bool BF16, bool NT>
 static hipError_t launch_mode(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
-    const bool has_v = a.v != nullptr;
     switch (a.mode) {
-    case kSesgd:
-        return has_v ? launch_one<VEC, BF16, true, NT, kSesgd>(a, s, stream)
-                     : launch_one<VEC, BF16, false, NT, kSesgd>(a, s, stream);
-    case kGradAvg:
-        return has_v ? launch_one<VEC, BF16, true, NT, kGradAvg>(a, s, stream)
-                     : launch_one<VEC, BF16, false, NT, kGradAvg>(a, s, stream);
+    case kSesgd: return launch_flags<VEC, BF16, NT, kSesgd>(a, s, stream);
+    case kGradAvg: return launch_flags<VEC, BF16, NT, kGradAvg>(a, s, stream);
     default:
         if constexpr (BF16) return hipErrorInvalidValue;
-        else return launch_one<VEC, false, false, NT, kAvgOnly>(a, s, stream);
+        else return launch_one<VEC, false, false, false, NT, kAvgOnly>(a, s, stream);
     }
 }
 

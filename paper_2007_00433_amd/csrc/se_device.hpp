@@ -85,12 +85,6 @@ __device__ __forceinline__ uint64_t next_row(uint64_t &todo)
     return r;
 }
 
-// Decayed gradient d = wd*x + g as one fused operation; g itself when wd == 0.
-__device__ __forceinline__ float decayed(float wd, float x, float g)
-{
-    return wd != 0.0f ? __builtin_fmaf(wd, x, g) : g;
-}
-
 // ---------------------------------------------------------------- row accessors
 template <int N> struct Pack { float a[N]; };
 

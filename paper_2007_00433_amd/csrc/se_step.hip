@@ -23,10 +23,9 @@
 namespace se {
 
 // ---- kSesgd: B members at once -------------------------------------------------------------
-template <int VEC, bool BF16, bool HAS_V, bool NT, int B>
+template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, bool NT, int B, bool FIRST>
 __device__ __forceinline__ void sesgd_batch(const StepArgs &p, uint64_t &todo, uint32_t off,
-                                            uint32_t goff, uint64_t gpitch_bytes,
-                                            Pack<VEC> &s, bool first)
+                                            uint32_t goff, uint64_t gpitch_bytes, Pack<VEC> &s)
 {
     uint64_t row[B];
 #pragma unroll
@@ -44,10 +43,10 @@ __device__ __forceinline__ void sesgd_batch(const StepArgs &p, uint64_t &todo, u
         Pack<VEC> vn;
 #pragma unroll
         for (int c = 0; c < VEC; ++c) {
-            const float d = decayed(p.wd, X[b].a[c], G[b].a[c]);
+            const float d = HAS_WD ? __builtin_fmaf(p.wd, X[b].a[c], G[b].a[c]) : G[b].a[c];
             vn.a[c] = HAS_V ? __builtin_fmaf(p.mu, V[b].a[c], d) : d;
             const float xhat = __builtin_fmaf(p.neg_lr, vn.a[c], X[b].a[c]);
-            s.a[c] = (first && b == 0) ? xhat : s.a[c] + xhat;
+            s.a[c] = (FIRST && b == 0) ? xhat : s.a[c] + xhat;
         }
         if constexpr (HAS_V)
             store_f32<VEC, NT>((char *)p.v + row[b] * p.pitch_bytes + off, vn);
@@ -55,9 +54,9 @@ __device__ __forceinline__ void sesgd_batch(const StepArgs &p, uint64_t &todo, u
 }
 
 // ---- kGradAvg / kAvgOnly, pass 1: sum one array over B members ---------------------------------
-template <int VEC, bool BF16, bool NT, bool PARAMS, int B>
+template <int VEC, bool BF16, bool NT, bool PARAMS, int B, bool FIRST>
 __device__ __forceinline__ void sum_batch(const StepArgs &p, uint64_t &todo, uint32_t off,
-                                          uint64_t pitch_bytes, Pack<VEC> &s, bool first)
+                                          uint64_t pitch_bytes, Pack<VEC> &s)
 {
     uint64_t row[B];
 #pragma unroll
@@ -72,11 +71,11 @@ __device__ __forceinline__ void sum_batch(const StepArgs &p, uint64_t &todo, uin
     for (int b = 0; b < B; ++b)
 #pragma unroll
         for (int c = 0; c < VEC; ++c)
-            s.a[c] = (first && b == 0) ? A[b].a[c] : s.a[c] + A[b].a[c];
+            s.a[c] = (FIRST && b == 0) ? A[b].a[c] : s.a[c] + A[b].a[c];
 }
 
 // ---- kGradAvg, pass 2: every member updates with the group's mean gradient ---------------------
-template <int VEC, bool HAS_V, bool NT, int B>
+template <int VEC, bool HAS_V, bool HAS_WD, bool NT, int B, bool FIRST>
 __device__ __forceinline__ void update_batch(const StepArgs &p, uint64_t &todo, uint32_t off,
                                              const Pack<VEC> &gbar)
 {
@@ -95,7 +94,7 @@ __device__ __forceinline__ void update_batch(const StepArgs &p, uint64_t &todo, 
         Pack<VEC> vn, xn;
 #pragma unroll
         for (int c = 0; c < VEC; ++c) {
-            const float d = decayed(p.wd, X[b].a[c], gbar.a[c]);
+            const float d = HAS_WD ? __builtin_fmaf(p.wd, X[b].a[c], gbar.a[c]) : gbar.a[c];
             vn.a[c] = HAS_V ? __builtin_fmaf(p.mu, V[b].a[c], d) : d;
             xn.a[c] = __builtin_fmaf(p.neg_lr, vn.a[c], X[b].a[c]);
         }
@@ -105,103 +104,111 @@ __device__ __forceinline__ void update_batch(const StepArgs &p, uint64_t &todo, 
     }
 }
 
-// Applies CALL(B) to all m members in batches of BMAX, then 4, 2, 1 (wave-uniform control).
+// Applies CALL(B, FIRST) to all m members in batches of BMAX, then 4, 2, 1; FIRST is true for
+// the batch that holds the group's first member (wave-uniform control flow throughout).
 #define SE_FOR_MEMBER_BATCHES(BMAX, m, CALL)                                               \
     do {                                                                                   \
         int rem_ = (m);                                                                    \
-        bool first = true;                                                                 \
-        while (rem_ >= BMAX) { CALL(BMAX); rem_ -= BMAX; first = false; }                  \
-        if constexpr (BMAX > 4) { if (rem_ >= 4) { CALL(4); rem_ -= 4; first = false; } }  \
-        if constexpr (BMAX > 2) { if (rem_ >= 2) { CALL(2); rem_ -= 2; first = false; } }  \
-        if constexpr (BMAX > 1) { if (rem_ >= 1) { CALL(1); } }                            \
-        (void)first;                                                                       \
+        bool first_ = true;                                                                \
+        if (rem_ >= BMAX) {                                                                \
+            CALL(BMAX, true); rem_ -= BMAX; first_ = false;                                \
+            while (rem_ >= BMAX) { CALL(BMAX, false); rem_ -= BMAX; }                      \
+        }                                                                                  \
+        if constexpr (BMAX > 4) { if (rem_ >= 4) {                                         \
+            if (first_) { CALL(4, true); } else { CALL(4, false); } rem_ -= 4; first_ = false; } } \
+        if constexpr (BMAX > 2) { if (rem_ >= 2) {                                         \
+            if (first_) { CALL(2, true); } else { CALL(2, false); } rem_ -= 2; first_ = false; } } \
+        if constexpr (BMAX > 1) { if (rem_ >= 1) {                                         \
+            if (first_) { CALL(1, true); } else { CALL(1, false); } } }                    \
     } while (0)
 
-template <int VEC, bool BF16, bool HAS_V, bool NT, int MODE, int BMAX>
+template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, bool NT, int MODE, int BMAX>
 __global__ __launch_bounds__(64) void se_step_kernel(const StepArgs p)
 {
     const int lane = (int)threadIdx.x;
     const uint64_t gpitch_bytes = BF16 ? p.pitch_bytes / 2 : p.pitch_bytes;
-    // workgroup -> (group g = blockIdx.y, run of consecutive tiles = blockIdx.x): all tiles of
-    // group 0 are dispatched first, then group 1, ...
-    const uint32_t g = blockIdx.y, chunk = blockIdx.x;
+    // workgroup -> (group g = blockIdx.y, tile = blockIdx.x): all tiles of group 0 are
+    // dispatched first, then group 1, ...
+    const uint32_t g = blockIdx.y;
     // Regrouping for this iteration, redone by every wavefront: ~150 instructions next to
     // ~20 KiB of memory traffic.
     const uint64_t members = wave_members(p.seed, p.iter, p.n, p.m, g, lane);
-    const uint32_t tile0 = chunk * p.tiles_per_block;
-    const uint32_t tile1 = min(tile0 + p.tiles_per_block, p.tiles);
 
-    for (uint32_t tile = tile0; tile < tile1; ++tile) {
-        const uint32_t c = tile * 64u + threadIdx.x;
-        if (c >= p.nvec) break;
-        const uint32_t off = c * (uint32_t)(VEC * 4);
-        const uint32_t goff = BF16 ? off / 2 : off;
+    const uint32_t c = blockIdx.x * 64u + threadIdx.x;
+    if (c >= p.nvec) return;
+    const uint32_t off = c * (uint32_t)(VEC * 4);
+    const uint32_t goff = BF16 ? off / 2 : off;
 
-        Pack<VEC> s;
+    Pack<VEC> s;
 #pragma unroll
-        for (int q = 0; q < VEC; ++q) s.a[q] = 0.0f;
-        uint64_t todo = members;
+    for (int q = 0; q < VEC; ++q) s.a[q] = 0.0f;
+    uint64_t todo = members;
 
-        if constexpr (MODE == kSesgd) {
-#define SE_CALL(B) sesgd_batch<VEC, BF16, HAS_V, NT, B>(p, todo, off, goff, gpitch_bytes, s, first)
-            SE_FOR_MEMBER_BATCHES(BMAX, p.m, SE_CALL);
+    if constexpr (MODE == kSesgd) {
+#define SE_CALL(B, F) sesgd_batch<VEC, BF16, HAS_V, HAS_WD, NT, B, F>(p, todo, off, goff, gpitch_bytes, s)
+        SE_FOR_MEMBER_BATCHES(BMAX, p.m, SE_CALL);
 #undef SE_CALL
-        } else if constexpr (MODE == kGradAvg) {
-#define SE_CALL(B) sum_batch<VEC, BF16, NT, false, B>(p, todo, goff, gpitch_bytes, s, first)
-            SE_FOR_MEMBER_BATCHES(8, p.m, SE_CALL);
+    } else if constexpr (MODE == kGradAvg) {
+#define SE_CALL(B, F) sum_batch<VEC, BF16, NT, false, B, F>(p, todo, goff, gpitch_bytes, s)
+        SE_FOR_MEMBER_BATCHES(8, p.m, SE_CALL);
 #undef SE_CALL
-        } else {
-#define SE_CALL(B) sum_batch<VEC, false, NT, true, B>(p, todo, off, p.pitch_bytes, s, first)
-            SE_FOR_MEMBER_BATCHES(8, p.m, SE_CALL);
+    } else {
+#define SE_CALL(B, F) sum_batch<VEC, false, NT, true, B, F>(p, todo, off, p.pitch_bytes, s)
+        SE_FOR_MEMBER_BATCHES(8, p.m, SE_CALL);
 #undef SE_CALL
-        }
+    }
 
-        Pack<VEC> mean;
+    Pack<VEC> mean;
 #pragma unroll
-        for (int q = 0; q < VEC; ++q) mean.a[q] = s.a[q] * p.inv_m;
-        todo = members;
-        if constexpr (MODE == kGradAvg) {
-#define SE_CALL(B) update_batch<VEC, HAS_V, NT, B>(p, todo, off, mean)
-            SE_FOR_MEMBER_BATCHES(4, p.m, SE_CALL);
+    for (int q = 0; q < VEC; ++q) mean.a[q] = s.a[q] * p.inv_m;
+    todo = members;
+    if constexpr (MODE == kGradAvg) {
+#define SE_CALL(B, F) update_batch<VEC, HAS_V, HAS_WD, NT, B, F>(p, todo, off, mean)
+        SE_FOR_MEMBER_BATCHES(4, p.m, SE_CALL);
 #undef SE_CALL
-        } else {
-            while (todo)
-                store_f32<VEC, NT>((char *)p.x + next_row(todo) * p.pitch_bytes + off, mean);
-        }
+    } else {
+        while (todo)
+            store_f32<VEC, NT>((char *)p.x + next_row(todo) * p.pitch_bytes + off, mean);
     }
 }
 
-template <int VEC, bool BF16, bool HAS_V, bool NT, int MODE, int BMAX>
+template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, bool NT, int MODE, int BMAX>
 static hipError_t launch_one(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
-    auto kern = se_step_kernel<VEC, BF16, HAS_V, NT, MODE, BMAX>;
+    auto kern = se_step_kernel<VEC, BF16, HAS_V, HAS_WD, NT, MODE, BMAX>;
     static std::atomic<uint64_t> allowed{0};
     if (s.lds_bytes > 0) {
         // the dynamic LDS is never touched: it only caps the resident workgroups per CU
         const hipError_t e = allow_full_lds((const void *)kern, allowed);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kern, dim3(a.chunks, (uint32_t)a.k), dim3(64), s.lds_bytes, stream, a);
+    hipLaunchKernelGGL(kern, dim3(a.tiles, (uint32_t)a.k), dim3(64), s.lds_bytes, stream, a);
     return hipGetLastError();
+}
+
+template <int VEC, bool BF16, bool NT, int MODE, int BMAX>
+static hipError_t launch_flags(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
+{
+    const bool has_v = a.v != nullptr, has_wd = a.wd != 0.0f;
+    if (has_v) return has_wd ? launch_one<VEC, BF16, true, true, NT, MODE, BMAX>(a, s, stream)
+                             : launch_one<VEC, BF16, true, false, NT, MODE, BMAX>(a, s, stream);
+    return has_wd ? launch_one<VEC, BF16, false, true, NT, MODE, BMAX>(a, s, stream)
+                  : launch_one<VEC, BF16, false, false, NT, MODE, BMAX>(a, s, stream);
 }
 
 template <int VEC, bool BF16, bool NT>
 static hipError_t launch_mode(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
-    const bool has_v = a.v != nullptr;
     switch (a.mode) {
     case kSesgd:
-        if (a.m >= 8)       // deeper batches keep more rows in flight for large groups
-            return has_v ? launch_one<VEC, BF16, true, NT, kSesgd, 8>(a, s, stream)
-                         : launch_one<VEC, BF16, false, NT, kSesgd, 8>(a, s, stream);
-        return has_v ? launch_one<VEC, BF16, true, NT, kSesgd, 4>(a, s, stream)
-                     : launch_one<VEC, BF16, false, NT, kSesgd, 4>(a, s, stream);
+        // deeper batches keep more rows in flight for large groups
+        return a.m >= 8 ? launch_flags<VEC, BF16, NT, kSesgd, 8>(a, s, stream)
+                        : launch_flags<VEC, BF16, NT, kSesgd, 4>(a, s, stream);
     case kGradAvg:
-        return has_v ? launch_one<VEC, BF16, true, NT, kGradAvg, 8>(a, s, stream)
-                     : launch_one<VEC, BF16, false, NT, kGradAvg, 8>(a, s, stream);
+        return launch_flags<VEC, BF16, NT, kGradAvg, 8>(a, s, stream);
     default:
         if constexpr (BF16) return hipErrorInvalidValue;
-        else return launch_one<VEC, false, false, NT, kAvgOnly, 8>(a, s, stream);
+        else return launch_one<VEC, false, false, false, NT, kAvgOnly, 8>(a, s, stream);
     }
 }
 

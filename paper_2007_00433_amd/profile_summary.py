@@ -21,15 +21,16 @@ import sys
 
 def kernel_key(name: str) -> str:
     """Classifies a kernel name.  The step kernels carry their mode as a template argument:
-    se_step_kernel<VEC, BF16, HAS_V, NT, MODE, BMAX> and se_coop_kernel<VEC, BF16, HAS_V, NT, MODE>
-    with MODE 0 = SESGD update, 1 = gradient averaging (the ring baseline), 2 = average only."""
+    se_step_kernel<VEC, BF16, HAS_V, HAS_WD, NT, MODE, BMAX> and
+    se_coop_kernel<VEC, BF16, HAS_V, HAS_WD, NT, MODE> with MODE 0 = SESGD update,
+    1 = gradient averaging (the ring baseline), 2 = average only."""
     for key in ("se_calib_copy_kernel", "se_plan_kernel", "se_consensus_kernel"):
         if key in name:
             return key
     for key in ("se_step_kernel", "se_coop_kernel"):
         if key in name and "<" in name:
             args = [a.strip() for a in name[name.index("<") + 1:name.index(">")].split(",")]
-            mode = {"0": "sesgd", "1": "ring", "2": "avgonly"}.get(args[4], args[4])
+            mode = {"0": "sesgd", "1": "ring", "2": "avgonly"}.get(args[5], args[5])
             return f"{mode}"
     return ""
 

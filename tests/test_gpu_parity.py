@@ -308,9 +308,7 @@ def test_results_do_not_depend_on_launch_knobs_or_stream():
     ref = None
     stream = torch.cuda.Stream()
     shapes = [dict(), dict(max_blocks_per_cu=0, nontemporal=0),
-              dict(tiles_per_block=3, max_blocks_per_cu=4),
-              dict(tiles_per_block=7, max_blocks_per_cu=1),
-              dict(tiles_per_block=1000, max_blocks_per_cu=32),
+              dict(max_blocks_per_cu=4), dict(max_blocks_per_cu=1), dict(max_blocks_per_cu=32),
               dict(coop_min_rows=0), dict(coop_min_rows=1), dict(coop_min_rows=2, max_blocks_per_cu=3),
               dict(coop_min_rows=16, nontemporal=0),
               dict(cache_resident_mib=0), dict(cache_resident_mib=0, coop_min_rows=1, max_blocks_per_cu=2)]
