@@ -25,7 +25,10 @@
  *     boundaries fall; the offsets define the pitch and are validated.
  *   - The three buffers must not overlap.  params and momentum are updated in place.
  *   - stream is a hipStream_t passed as void* (NULL = the default stream).  se_step and
- *     se_ring_step only enqueue work on it and return without synchronising.
+ *     se_ring_step only enqueue work on it and return without synchronising.  They record
+ *     kernel launches only (no memset, no allocation), so they may be captured in a HIP graph;
+ *     the first launch of each kernel variant on a device also sets a function attribute, so
+ *     make one ordinary call with the same argument types before capturing.
  *   - fp32 arithmetic, round-to-nearest-even, denormals kept, with this fixed order per
  *     element e and group with members j_0 < j_1 < ... (ascending worker id):
  *         v'_j   = fma(mu, v_j, g_j)            (g_j if momentum == NULL)
