@@ -257,6 +257,24 @@ def main():
         torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(w, pitch, args.cpu_seconds)
     if args.all_workloads:
+        # The paper's schedule sends layer l while backward computes layer l-1 (Sec. 2.1) and pays
+        # a fixed latency per layer (Sec. 2.3).  The GPU analogue: one se_step_ex call per tensor,
+        # back to front, against the single fused launch timed above.
+        L = len(w.sizes)
+
+        def launch_per_layer(t, stream):
+            for l in range(L - 1, -1, -1):
+                se.se_step_ex(x, pool[t % len(pool)], v, offs, n, m, t, w.lr, w.mu, 0.0, 0,
+                              first_layer=l, last_layer=l + 1, grads_are_bf16=bf16, stream=stream)
+
+        if not args.skip_cpu_baseline:          # x, v, pool were released above
+            x = torch.zeros(n, pitch, device="cuda")
+            v = torch.zeros(n, pitch, device="cuda")
+            pool = [torch.zeros(n, pitch, device="cuda", dtype=torch.bfloat16 if bf16 else torch.float32)]
+        lwall, _ = timed_steps(launch_per_layer, max(5, args.steps // 5), 2, torch)
+        out["per_layer_schedule"] = {"launch_calls_per_step": L,
+                                     "steps_per_s": round(max(5, args.steps // 5) / lwall, 3),
+                                     "fused_over_per_layer": round(out["value"] * lwall / max(5, args.steps // 5), 3)}
         out["all_workloads"] = {}
         for name in ("tiny", "resnet20", "resnet50", "vgg16", "bert_base", "bert_base_full"):
             out["all_workloads"][name] = measure_workload(
