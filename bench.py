@@ -194,14 +194,18 @@ def main():
     bytes_per_launch = se.se_step_bytes(pitch, n, w.grad_bytes, True)
     achieved = bytes_per_launch / per_launch / 1e9
 
-    # HBM bytes per launch measured offline with rocprofv3 --pmc (see profiles/*.md)
+    # HBM bytes per launch measured offline with rocprofv3 --pmc: the `sesgd` row of the traffic
+    # table in profiles/se_step_<workload>_n<n>_m<m>.md (written by profile_summary.py)
     traffic = None
-    prof = os.path.join(ROOT, "profiles", f"se_step_{args.workload}_n{n}_m{m}.json")
+    prof = os.path.join(ROOT, "profiles", f"se_step_{args.workload}_n{n}_m{m}.md")
     if os.path.exists(prof):
         with open(prof) as f:
-            pj = json.load(f)
-        if pj.get("pitch") == pitch:
-            traffic = pj["kernels"].get("sesgd", {}).get("traffic_bytes")
+            text = f.read()
+        if f"pitch={pitch})" in text:
+            for line in text.splitlines():
+                cells = [c.strip() for c in line.split("|")]
+                if len(cells) == 10 and cells[1] == "sesgd" and cells[6].isdigit():
+                    traffic = int(cells[6])
 
     out = {
         "metric": "SESGD steps/sec and achieved HBM GB/s (% of peak), n=16 ResNet-50-shaped"

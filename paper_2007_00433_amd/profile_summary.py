@@ -1,5 +1,5 @@
 """Turns rocprofv3 CSV output of `bench.py` runs into the short text summaries kept under
-profiles/ and the small JSON that bench.py reads for its `roofline.traffic` field.
+profiles/ (bench.py reads its `roofline.traffic` figure from the traffic table in them).
 
     python -m paper_2007_00433_amd.profile_summary <dir with stats/ fetch/ write/> <workload> <out stem>
 
@@ -14,7 +14,6 @@ from __future__ import annotations
 
 import collections
 import csv
-import json
 import os
 import sys
 
@@ -111,8 +110,6 @@ def main():
                                                  "traffic_bytes": rb + wb})
     with open(stem + ".md", "w") as f:
         f.write("\n".join(lines) + "\n")
-    with open(stem + ".json", "w") as f:
-        json.dump(out, f, indent=1)
     print("\n".join(lines))
 
 
