@@ -657,3 +657,42 @@ def test_maximum_row_length_sampled():
         assert bit_mismatches(v[:, cols].cpu().numpy(), hv) == 0
         del x, v, g, xb, vb, gb
         torch.cuda.empty_cache()
+
+
+def test_randomised_configurations():
+    """Sixty seeded random combinations of worker count, group size, width, gradient storage,
+    momentum buffer, weight decay, mode, base-address shift, layer range and launch knobs."""
+    rng = np.random.default_rng(2007_00433)
+    defaults = {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}
+    for case_no in range(60):
+        n = int(rng.integers(1, 65))
+        m = int(rng.choice(divisors(n)))
+        ncols = int(rng.choice([1, 3, 17, 64, 255, 256, 300, 1025, 4100]))
+        dtype = str(rng.choice(["f32", "bf16"]))
+        use_v = bool(rng.integers(0, 2))
+        wd = float(rng.choice([0.0, 1e-4, 5e-4]))
+        flags = GA if rng.integers(0, 3) == 0 else 0
+        shift = int(rng.choice([0, 0, 1, 2, 4]))
+        knobs = dict(coop_min_rows=int(rng.choice([0, 1, 8, 16])), nontemporal=int(rng.integers(0, 2)),
+                     max_blocks_per_cu=int(rng.choice([0, 1, 6, 32])), cache_resident_mib=int(rng.choice([0, 192])))
+        for k, val in {**defaults, **knobs}.items():
+            se.se_set_tuning(k, val)
+        se.se_set_seed(int(rng.integers(0, 2 ** 63)))
+        # three layers with random boundaries
+        cuts = sorted(int(c) for c in rng.integers(0, ncols + 1, size=2))
+        sizes = [cuts[0], cuts[1] - cuts[0], ncols - cuts[1]]
+        first = int(rng.integers(0, 3)); last = int(rng.integers(first, 4))
+        what = f"case {case_no}: n={n} m={m} cols={ncols} {dtype} v={use_v} wd={wd} flags={flags} shift={shift} " \
+               f"sizes={sizes} layers=[{first},{last}) knobs={knobs}"
+        say(what)
+        case = Case(n, ncols, dtype=dtype, use_v=use_v, shift=shift, distinct_rows=True, v_std=0.01 if use_v else 0.0)
+        offs = case.offsets(sizes)
+        mu = 0.9 if use_v else 0.0
+        for t in range(2):
+            hg = case.grads(t, 1e-2)
+            it = int(rng.integers(0, 2 ** 40))
+            se.se_step_ex(case.dx, case.dg, case.dv, offs, n, m, it, 0.1, mu, wd, flags,
+                          first_layer=first, last_layer=last, grads_are_bf16=(dtype == "bf16"))
+            oracle.step_ex(case.hx, hg, case.hv, m, it, 0.1, mu, wd, flags, seed=se.se_get_seed(),
+                           cols=(offs[first], offs[last]))
+        case.check(what)
