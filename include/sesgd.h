@@ -191,6 +191,8 @@ int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
  *                         se_global_average) from which the rows are split over the wavefronts
  *                         of a workgroup and the values to reduce are staged in LDS; below it
  *                         one wavefront owns all rows of its group.  0 = never (default 8)
+ *   "coop_tiles"          cooperative form: consecutive 64-lane tiles one workgroup walks through;
+ *                         0 = chosen by group size: 4 above 32 rows, else 1 (default 0)
  *   "cache_resident_mib"  a launch that moves fewer MiB than this (default 192; the Infinity
  *                         Cache holds 256 MiB) uses plain accesses and no residency cap, which
  *                         is faster when nothing streams from HBM; 0 = always stream

@@ -16,6 +16,7 @@ std::atomic<uint64_t> g_seed{0};
 std::atomic<int> g_nontemporal{1};
 std::atomic<int> g_max_blocks_per_cu{6};  // resident workgroups per CU (0 = no cap)
 std::atomic<int> g_coop_min_rows{8};      // rows reduced together from which the LDS form is used (0 = never)
+std::atomic<int> g_coop_tiles{0};         // cooperative form: consecutive tiles per workgroup (0 = by group size)
 std::atomic<int> g_cache_resident_mib{192};  // launches moving fewer MiB stay in the 256 MiB Infinity Cache
 
 thread_local char t_last_error[256] = "";
@@ -86,6 +87,8 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     a.pitch_bytes = (uint64_t)j.pitch * 4u;
     a.nvec = (uint32_t)((c1 - c0) / vec);
     a.tiles = (a.nvec + 63u) / 64u;
+    const int coop_tiles = g_coop_tiles.load();
+    a.coop_tiles = coop_tiles > 0 ? (uint32_t)coop_tiles : (j.m > 32 ? 4u : 1u);
     a.n = j.n; a.m = j.m; a.k = j.n / j.m;
     a.neg_lr = -j.lr; a.mu = j.mu; a.inv_m = 1.0f / (float)j.m; a.wd = j.wd;
     a.mode = j.mode;
@@ -164,6 +167,7 @@ Knob kKnobs[] = {
     {"max_blocks_per_cu", &g_max_blocks_per_cu, 0, 32},
     {"nontemporal", &g_nontemporal, 0, 1},
     {"coop_min_rows", &g_coop_min_rows, 0, 65},
+    {"coop_tiles", &g_coop_tiles, 0, 4096},
     {"cache_resident_mib", &g_cache_resident_mib, 0, 1 << 20},
 };
 

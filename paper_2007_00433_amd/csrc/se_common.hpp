@@ -27,6 +27,7 @@ struct StepArgs {
     uint64_t pitch_bytes;      // row distance of x and v in bytes (half of it for bf16 g)
     uint32_t nvec;
     uint32_t tiles;
+    uint32_t coop_tiles;       // cooperative form: consecutive tiles one workgroup walks through
     int n, m, k;               // workers, rows reduced together, groups
     float neg_lr, mu, inv_m, wd;
     int mode;                  // Mode
@@ -42,7 +43,7 @@ struct LaunchShape {
 // single-wavefront form: grid (a.tiles, a.k)
 hipError_t launch_step(const StepArgs &a, const LaunchShape &s, hipStream_t stream);
 // cooperative form: a.m rows reduced together by ceil(a.m / 4) wavefronts per workgroup,
-// grid (a.tiles, a.k)
+// grid (ceil(a.tiles / a.coop_tiles), a.k)
 hipError_t launch_coop(const StepArgs &a, const LaunchShape &s, hipStream_t stream);
 hipError_t launch_plan(uint64_t seed, int64_t iter, int n, int m, int32_t *group_of_dev,
                        int32_t *members_dev, hipStream_t stream);

@@ -27,13 +27,8 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
     const int wave = (int)(threadIdx.x >> 6);
     const uint64_t gpitch_bytes = BF16 ? p.pitch_bytes / 2 : p.pitch_bytes;
 
-    const uint32_t g = blockIdx.y, tile = blockIdx.x;
+    const uint32_t g = blockIdx.y;
     const uint64_t members = wave_members(p.seed, p.iter, p.n, p.m, g, lane);
-
-    const uint32_t c = tile * 64u + (uint32_t)lane;
-    const bool valid = c < p.nvec;
-    const uint32_t off = c * (uint32_t)(VEC * 4);
-    const uint32_t goff = BF16 ? off / 2 : off;
 
     // this wavefront's rows: members number wave*kRowsPerWave .. +kRowsPerWave-1
     const int first = wave * kRowsPerWave;
@@ -46,6 +41,16 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
         row[r] = todo ? (uint64_t)__builtin_ctzll(todo) : 0;
         todo &= todo - 1;
     }
+
+    // A workgroup walks through coop_tiles consecutive tiles.  One tile per workgroup keeps
+    // neighbouring tiles in flight together, which DRAM likes best; only with very many rows
+    // (192 row streams at m = 64) a few tiles per workgroup measure faster.
+    const uint32_t tile_end = min((blockIdx.x + 1u) * p.coop_tiles, p.tiles);
+  for (uint32_t tile = blockIdx.x * p.coop_tiles; tile < tile_end; ++tile) {
+    const uint32_t c = tile * 64u + (uint32_t)lane;
+    const bool valid = c < p.nvec;
+    const uint32_t off = c * (uint32_t)(VEC * 4);
+    const uint32_t goff = BF16 ? off / 2 : off;
 
     Pack<VEC> X[kRowsPerWave], G[kRowsPerWave], V[kRowsPerWave];
     if (valid) {
@@ -84,8 +89,7 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
         }
     }
     __syncthreads();
-    if (!valid) return;
-
+    if (valid) {
     Pack<VEC> s = load_f32<VEC, false>((const char *)(staged + (size_t)lane * VEC));
     for (int r = 1; r < p.m; ++r) {
         const Pack<VEC> t = load_f32<VEC, false>((const char *)(staged + ((size_t)r * 64 + lane) * VEC));
@@ -115,6 +119,9 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
             }
         }
     }
+    }
+    __syncthreads();        // the staging area is rewritten by the next tile
+  }
 }
 
 template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, bool NT, int MODE>
@@ -127,7 +134,8 @@ static hipError_t launch_one(const StepArgs &a, const LaunchShape &s, hipStream_
     static std::atomic<uint64_t> allowed{0};
     const hipError_t e = allow_full_lds((const void *)kern, allowed);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(a.tiles, (uint32_t)a.k), dim3(waves * 64), lds, stream, a);
+    hipLaunchKernelGGL(kern, dim3((a.tiles + a.coop_tiles - 1) / a.coop_tiles, (uint32_t)a.k),
+                       dim3(waves * 64), lds, stream, a);
     return hipGetLastError();
 }
 

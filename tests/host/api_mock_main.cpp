@@ -39,6 +39,7 @@ hipError_t record(const se::StepArgs &a, const se::LaunchShape &s, bool coop)
     if (coop) {
         EXPECT((size_t)a.m * 64 * s.vec * 4 <= 64u * 1024u);               // staging fits
         EXPECT((a.m + 3) / 4 <= 16);                                       // <= 1024 threads
+        EXPECT(a.coop_tiles >= 1);
     }
     g_recs.push_back({(uintptr_t)a.x, (uintptr_t)a.g, (uintptr_t)a.v, (uint64_t)a.nvec * (uint64_t)s.vec,
                       s.vec, coop, s.bf16, a.mode, a.m, a.k, a.tiles});

@@ -311,7 +311,9 @@ def test_results_do_not_depend_on_launch_knobs_or_stream():
               dict(max_blocks_per_cu=4), dict(max_blocks_per_cu=1), dict(max_blocks_per_cu=32),
               dict(coop_min_rows=0), dict(coop_min_rows=1), dict(coop_min_rows=2, max_blocks_per_cu=3),
               dict(coop_min_rows=16, nontemporal=0),
-              dict(cache_resident_mib=0), dict(cache_resident_mib=0, coop_min_rows=1, max_blocks_per_cu=2)]
+              dict(cache_resident_mib=0), dict(cache_resident_mib=0, coop_min_rows=1, max_blocks_per_cu=2),
+              dict(coop_min_rows=1, coop_tiles=1), dict(coop_min_rows=1, coop_tiles=7),
+              dict(coop_min_rows=1, coop_tiles=4096)]
     defaults = {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}
     for q, shape in enumerate(shapes):
         for k, val in {**defaults, **shape}.items():
@@ -674,6 +676,7 @@ def test_randomised_configurations():
         flags = GA if rng.integers(0, 3) == 0 else 0
         shift = int(rng.choice([0, 0, 1, 2, 4]))
         knobs = dict(coop_min_rows=int(rng.choice([0, 1, 8, 16])), nontemporal=int(rng.integers(0, 2)),
+                     coop_tiles=int(rng.choice([1, 2, 4, 5, 64])),
                      max_blocks_per_cu=int(rng.choice([0, 1, 6, 32])), cache_resident_mib=int(rng.choice([0, 192])))
         for k, val in {**defaults, **knobs}.items():
             se.se_set_tuning(k, val)
