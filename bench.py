@@ -61,6 +61,20 @@ def timed_steps(launch, steps, warmup, torch):
     return wall, ev0.elapsed_time(ev1) * 1e-3 / steps
 
 
+def per_launch_ms(launch, steps, first_iter, torch):
+    """One stream-event pair around every launch (iterations first_iter, first_iter+1, ...);
+    returns the sorted launch durations in ms."""
+    stream = torch.cuda.current_stream()
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+             for _ in range(steps)]
+    for t, (e0, e1) in enumerate(pairs):
+        e0.record(stream)
+        launch(first_iter + t, stream)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    return sorted(e0.elapsed_time(e1) for e0, e1 in pairs)
+
+
 def cpu_baseline(w, pitch, target_seconds):
     """The oracle as it stands, on a column slice of the same workload, timed on this host:
     once from a single thread, once from one thread per available core on disjoint column
@@ -127,7 +141,7 @@ def measure_workload(name, steps, warmup, cpu_seconds, torch, se, wl):
             g[i, :P] = (torch.randn(P, device="cuda", generator=gen) * w.grad_std).to(g.dtype)
         pool.append(g)
     mu = w.mu if w.mu else 0.9          # the tiny config has mu = 0: time it with a momentum buffer anyway
-    nbytes = se.se_step_bytes(pitch, n, w.grad_bytes, True)
+    nbytes = se.se_step_bytes(P, n, w.grad_bytes, True)
     k = max(steps, 20) if nbytes < 1e9 else max(5, steps // 5) if nbytes > 2e10 else steps
     _, per = timed_steps(lambda t, s: step_fn(x, pool[t % 2], v, offs, n, m, t, w.lr, mu, s), k, warmup, torch)
     _, rper = timed_steps(lambda t, s: ring_fn(x, pool[t % 2], v, offs, n, w.lr, mu, s), k, warmup, torch)
@@ -191,8 +205,10 @@ def main():
         ring_fn(x, pool[t % len(pool)], v, offs, n, w.lr, w.mu, stream)
 
     wall, per_launch = timed_steps(launch_step, args.steps, args.warmup, torch)
-    bytes_per_launch = se.se_step_bytes(pitch, n, w.grad_bytes, True)
+    bytes_per_launch = se.se_step_bytes(P, n, w.grad_bytes, True)
     achieved = bytes_per_launch / per_launch / 1e9
+    # spread of single launches, outside the timed region: median and fastest of the same count
+    each = per_launch_ms(launch_step, args.steps, args.warmup + args.steps, torch)
 
     # HBM bytes per launch measured offline with rocprofv3 --pmc: the `sesgd` row of the traffic
     # table in profiles/se_step_<workload>_n<n>_m<m>.md (written by profile_summary.py)
@@ -225,7 +241,9 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "se_step_kernel" if m < se.se_get_tuning("coop_min_rows") or se.se_get_tuning("coop_min_rows") == 0 else "se_coop_kernel", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "bytes_per_launch": bytes_per_launch,
-                     "avg_launch_ms": round(per_launch * 1e3, 5)},
+                     "avg_launch_ms": round(per_launch * 1e3, 5),
+                     "median_launch_ms": round(each[len(each) // 2], 5),
+                     "min_launch_ms": round(each[0], 5)},
     }
     # practical ceiling: a plain streaming copy over buffers of the same size
     nb = pool[0].numel() * pool[0].element_size()

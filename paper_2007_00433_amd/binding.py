@@ -155,8 +155,8 @@ def se_pitch(P: int) -> int:
     return int(lib.se_pitch(P))
 
 
-def se_step_bytes(pitch: int, n: int, grad_elem_bytes: int = 4, has_momentum: bool = True) -> int:
-    return int(lib.se_step_bytes(pitch, n, grad_elem_bytes, int(has_momentum)))
+def se_step_bytes(columns: int, n: int, grad_elem_bytes: int = 4, has_momentum: bool = True) -> int:
+    return int(lib.se_step_bytes(columns, n, grad_elem_bytes, int(has_momentum)))
 
 
 def se_set_tuning(name: str, value: int) -> None:

@@ -311,13 +311,13 @@ uint64_t se_get_seed(void) { return g_seed.load(); }
 int64_t se_pitch(int64_t P)
 {
     if (P < 0) return -1;
-    return (P + 63) / 64 * 64;
+    return (P + 1023) / 1024 * 1024;
 }
 
-int64_t se_step_bytes(int64_t pitch, int n, int grad_elem_bytes, int has_momentum)
+int64_t se_step_bytes(int64_t columns, int n, int grad_elem_bytes, int has_momentum)
 {
-    if (pitch < 0 || n < 0 || (grad_elem_bytes != 2 && grad_elem_bytes != 4)) return -1;
-    return (int64_t)n * pitch * (8 + grad_elem_bytes + (has_momentum ? 8 : 0));
+    if (columns < 0 || n < 0 || (grad_elem_bytes != 2 && grad_elem_bytes != 4)) return -1;
+    return (int64_t)n * columns * (8 + grad_elem_bytes + (has_momentum ? 8 : 0));
 }
 
 int se_set_tuning(const char *name, int value)

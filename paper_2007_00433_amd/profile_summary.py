@@ -49,9 +49,9 @@ def main():
     sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
     from paper_2007_00433_amd import workloads as wl
     w = wl.WORKLOADS[workload]
-    pitch = (w.P + 63) // 64 * 64
-    rd = w.n * pitch * (8 + w.grad_bytes)
-    wr = w.n * pitch * 8
+    pitch = (w.P + 1023) // 1024 * 1024              # se_pitch(P)
+    rd = w.n * w.P * (8 + w.grad_bytes)              # algorithmic: the P real elements per worker
+    wr = w.n * w.P * 8
     copy_bytes = w.n * pitch * w.grad_bytes          # bench.py copies one gradient buffer
 
     stats = {}

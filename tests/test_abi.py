@@ -38,8 +38,8 @@ def test_error_strings():
 
 
 def test_pitch_and_bytes():
-    assert se.se_pitch(0) == 0 and se.se_pitch(1) == 64 and se.se_pitch(64) == 64
-    assert se.se_pitch(5106) == 5120 and se.se_pitch(25557032) == 25557056
+    assert se.se_pitch(0) == 0 and se.se_pitch(1) == 1024 and se.se_pitch(1024) == 1024
+    assert se.se_pitch(5106) == 5120 and se.se_pitch(25557032) == 25558016
     assert se.se_pitch(-1) == -1
     assert se.se_step_bytes(25557032, 16, 4, True) == 8178250240      # headline config
     assert se.se_step_bytes(109482240, 64, 2, True) == 126123540480   # bf16 gradients
