@@ -171,7 +171,7 @@ def run_ring(case, iters, lr, mu, grad_std, stream=None):
 # ------------------------------------------------------------------------ step parity
 @pytest.mark.parametrize("use_v", [False, True])
 def test_config_tiny(use_v):
-    """BASELINE config 1: n=4, m=2, tensors [1000, 4096, 10], mu=0, 5 iterations; run both
+    """Tiny configuration: n=4, m=2, tensors [1000, 4096, 10], mu=0, 5 iterations; run both
     without a momentum buffer and with a zero buffer."""
     w = wl.WORKLOADS["tiny"]
     case = Case(w.n, w.P, use_v=use_v)
@@ -180,7 +180,7 @@ def test_config_tiny(use_v):
 
 
 def test_config_resnet20():
-    """BASELINE config 2: n=16, m=4, ResNet-20-shaped (P = 269722, rows only 8-byte aligned),
+    """ResNet-20-shaped configuration: n=16, m=4, ResNet-20-shaped (P = 269722, rows only 8-byte aligned),
     100 iterations with momentum."""
     w = wl.WORKLOADS["resnet20"]
     assert w.P == 269722

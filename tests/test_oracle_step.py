@@ -331,7 +331,7 @@ def test_column_range_touches_only_its_columns():
 
 
 def test_configs_run_and_stay_finite():
-    """BASELINE config 1 end to end on the oracle (well under a second)."""
+    """The tiny configuration end to end on the oracle (well under a second)."""
     w = wl.WORKLOADS["tiny"]
     x, _ = _run(w.n, w.group_size, w.P, w.iters, w.lr, w.mu, use_v=False, grad_std=w.grad_std)
     assert np.isfinite(x).all()
