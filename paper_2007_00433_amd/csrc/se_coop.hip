@@ -46,82 +46,84 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
     // neighbouring tiles in flight together, which DRAM likes best; only with very many rows
     // (192 row streams at m = 64) a few tiles per workgroup measure faster.
     const uint32_t tile_end = min((blockIdx.x + 1u) * p.coop_tiles, p.tiles);
-  for (uint32_t tile = blockIdx.x * p.coop_tiles; tile < tile_end; ++tile) {
-    const uint32_t c = tile * 64u + (uint32_t)lane;
-    const bool valid = c < p.nvec;
-    const uint32_t off = c * (uint32_t)(VEC * 4);
-    const uint32_t goff = BF16 ? off / 2 : off;
+    for (uint32_t tile = blockIdx.x * p.coop_tiles; tile < tile_end; ++tile) {
+        const uint32_t c = tile * 64u + (uint32_t)lane;
+        const bool valid = c < p.nvec;
+        const uint32_t off = c * (uint32_t)(VEC * 4);
+        const uint32_t goff = BF16 ? off / 2 : off;
 
-    Pack<VEC> X[kRowsPerWave], G[kRowsPerWave], V[kRowsPerWave];
-    if (valid) {
+        Pack<VEC> X[kRowsPerWave], G[kRowsPerWave], V[kRowsPerWave];
+        if (valid) {
 #pragma unroll
-        for (int r = 0; r < kRowsPerWave; ++r) {
-            if (r < mine) {
-                X[r] = load_f32<VEC, NT>((const char *)p.x + row[r] * p.pitch_bytes + off);
-                if constexpr (MODE != kAvgOnly) {
-                    G[r] = load_grad<VEC, BF16, NT>((const char *)p.g + row[r] * gpitch_bytes + goff);
-                    if constexpr (HAS_V)
-                        V[r] = load_f32<VEC, NT>((const char *)p.v + row[r] * p.pitch_bytes + off);
-                }
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < kRowsPerWave; ++r) {
-            if (r < mine) {
-                Pack<VEC> out;
-                if constexpr (MODE == kGradAvg) {
-                    out = G[r];
-                } else if constexpr (MODE == kAvgOnly) {
-                    out = X[r];
-                } else {
-                    Pack<VEC> vn;
-#pragma unroll
-                    for (int q = 0; q < VEC; ++q) {
-                        const float d = HAS_WD ? __builtin_fmaf(p.wd, X[r].a[q], G[r].a[q]) : G[r].a[q];
-                        vn.a[q] = HAS_V ? __builtin_fmaf(p.mu, V[r].a[q], d) : d;
-                        out.a[q] = __builtin_fmaf(p.neg_lr, vn.a[q], X[r].a[q]);
+            for (int r = 0; r < kRowsPerWave; ++r) {
+                if (r < mine) {
+                    X[r] = load_f32<VEC, NT>((const char *)p.x + row[r] * p.pitch_bytes + off);
+                    if constexpr (MODE != kAvgOnly) {
+                        G[r] = load_grad<VEC, BF16, NT>((const char *)p.g + row[r] * gpitch_bytes + goff);
+                        if constexpr (HAS_V)
+                            V[r] = load_f32<VEC, NT>((const char *)p.v + row[r] * p.pitch_bytes + off);
                     }
-                    if constexpr (HAS_V)
-                        store_f32<VEC, NT>((char *)p.v + row[r] * p.pitch_bytes + off, vn);
                 }
-                store_f32<VEC, false>((char *)(staged + ((size_t)(first + r) * 64 + lane) * VEC), out);
+            }
+#pragma unroll
+            for (int r = 0; r < kRowsPerWave; ++r) {
+                if (r < mine) {
+                    Pack<VEC> out;
+                    if constexpr (MODE == kGradAvg) {
+                        out = G[r];
+                    } else if constexpr (MODE == kAvgOnly) {
+                        out = X[r];
+                    } else {
+                        Pack<VEC> vn;
+#pragma unroll
+                        for (int q = 0; q < VEC; ++q) {
+                            const float d = HAS_WD ? __builtin_fmaf(p.wd, X[r].a[q], G[r].a[q]) : G[r].a[q];
+                            vn.a[q] = HAS_V ? __builtin_fmaf(p.mu, V[r].a[q], d) : d;
+                            out.a[q] = __builtin_fmaf(p.neg_lr, vn.a[q], X[r].a[q]);
+                        }
+                        if constexpr (HAS_V)
+                            store_f32<VEC, NT>((char *)p.v + row[r] * p.pitch_bytes + off, vn);
+                    }
+                    store_f32<VEC, false>((char *)(staged + ((size_t)(first + r) * 64 + lane) * VEC), out);
+                }
             }
         }
-    }
-    __syncthreads();
-    if (valid) {
-    Pack<VEC> s = load_f32<VEC, false>((const char *)(staged + (size_t)lane * VEC));
-    for (int r = 1; r < p.m; ++r) {
-        const Pack<VEC> t = load_f32<VEC, false>((const char *)(staged + ((size_t)r * 64 + lane) * VEC));
+        __syncthreads();
+        if (valid) {
+            Pack<VEC> s = load_f32<VEC, false>((const char *)(staged + (size_t)lane * VEC));
+            for (int r = 1; r < p.m; ++r) {
+                const Pack<VEC> t = load_f32<VEC, false>((const char *)(staged + ((size_t)r * 64 + lane) * VEC));
 #pragma unroll
-        for (int q = 0; q < VEC; ++q) s.a[q] = s.a[q] + t.a[q];
-    }
-    Pack<VEC> mean;
+                for (int q = 0; q < VEC; ++q) s.a[q] = s.a[q] + t.a[q];
+            }
+            Pack<VEC> mean;
 #pragma unroll
-    for (int q = 0; q < VEC; ++q) mean.a[q] = s.a[q] * p.inv_m;
+            for (int q = 0; q < VEC; ++q) mean.a[q] = s.a[q] * p.inv_m;
 
 #pragma unroll
-    for (int r = 0; r < kRowsPerWave; ++r) {
-        if (r < mine) {
-            if constexpr (MODE == kGradAvg) {
-                Pack<VEC> vn, xn;
+            for (int r = 0; r < kRowsPerWave; ++r) {
+                if (r < mine) {
+                    if constexpr (MODE == kGradAvg) {
+                        Pack<VEC> vn, xn;
 #pragma unroll
-                for (int q = 0; q < VEC; ++q) {
-                    const float d = HAS_WD ? __builtin_fmaf(p.wd, X[r].a[q], mean.a[q]) : mean.a[q];
-                    vn.a[q] = HAS_V ? __builtin_fmaf(p.mu, V[r].a[q], d) : d;
-                    xn.a[q] = __builtin_fmaf(p.neg_lr, vn.a[q], X[r].a[q]);
+                        for (int q = 0; q < VEC; ++q) {
+                            const float d = HAS_WD ? __builtin_fmaf(p.wd, X[r].a[q], mean.a[q]) : mean.a[q];
+                            vn.a[q] = HAS_V ? __builtin_fmaf(p.mu, V[r].a[q], d) : d;
+                            xn.a[q] = __builtin_fmaf(p.neg_lr, vn.a[q], X[r].a[q]);
+                        }
+                        if constexpr (HAS_V)
+                            store_f32<VEC, NT>((char *)p.v + row[r] * p.pitch_bytes + off, vn);
+                        store_f32<VEC, NT>((char *)p.x + row[r] * p.pitch_bytes + off, xn);
+                    } else {
+                        store_f32<VEC, NT>((char *)p.x + row[r] * p.pitch_bytes + off, mean);
+                    }
                 }
-                if constexpr (HAS_V)
-                    store_f32<VEC, NT>((char *)p.v + row[r] * p.pitch_bytes + off, vn);
-                store_f32<VEC, NT>((char *)p.x + row[r] * p.pitch_bytes + off, xn);
-            } else {
-                store_f32<VEC, NT>((char *)p.x + row[r] * p.pitch_bytes + off, mean);
             }
         }
+        // the staging area is rewritten by the next tile (uniform: every thread of the
+        // workgroup runs the same number of tiles)
+        if (tile + 1 < tile_end) __syncthreads();
     }
-    }
-    __syncthreads();        // the staging area is rewritten by the next tile
-  }
 }
 
 template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, bool NT, int MODE>
