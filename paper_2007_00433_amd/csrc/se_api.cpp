@@ -102,11 +102,9 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     const uint64_t moved = (uint64_t)j.n * (uint64_t)(c1 - c0) * per_elem;
     const bool streams = moved >= ((uint64_t)g_cache_resident_mib.load() << 20);
     s.nontemporal = streams && g_nontemporal.load() != 0;
-    int cap = streams ? g_max_blocks_per_cu.load() : 0;
+    const int cap = streams ? g_max_blocks_per_cu.load() : 0;
     const int coop = g_coop_min_rows.load();
     const bool use_coop = coop > 0 && j.m >= coop;
-    // cooperative workgroups of 4 or more wavefronts (m > 12): 3 resident ones measured best
-    if (use_coop && cap > 3 && j.m > 12) cap = 3;
     s.lds_bytes = cap > 0 ? (se::kLdsPerCu / (uint32_t)cap) & ~1023u : 0u;
     if (use_coop) return se::launch_coop(a, s, j.stream);
     return se::launch_step(a, s, j.stream);

@@ -2,13 +2,22 @@
 // and of its "consistency of parameters" experiment, Sec. 4.2), in double precision:
 //   out[0] += sum_e sum_i (x_i[e] - xbar[e])^2,  xbar[e] = (sum_i x_i[e]) / n   (Sec. 3.3)
 //   out[1] += sum_e sum_i x_i[e]
-// A lane owns a column at a time (rows re-read for the deviations; the second read is served
-// by the caches), partial sums are reduced across the wavefront with lane shuffles, across
-// the wavefronts of the workgroup through LDS, and one fp64 atomic per workgroup and output
-// adds them to the caller's two doubles, which a one-lane kernel cleared before.
+//
+// Every element is read once.  A lane owns VEC columns of a 64-lane tile and walks the n rows
+// in batches of 8 loads; the squared deviations are taken about row 0 instead of the mean,
+//   sum_i (x_i - xbar)^2 = sum_i d_i^2 - (sum_i d_i)^2 / n,   d_i = x_i - x_0,
+// where every d_i is exact in double precision (a difference of two floats), the right-hand
+// side cancels at most a factor n (x_0 is one of the samples), and identical rows give exactly
+// zero.  Workgroups of one wavefront stride over the tiles so that the tiles in flight are
+// neighbours; partial sums are reduced across the wavefront with lane shuffles and added to the
+// caller's two doubles with one fp64 atomic each per workgroup; a one-lane kernel clears them
+// first.
 #include "se_device.hpp"
 
 namespace se {
+
+constexpr uint32_t kConsensusMaxGrid = 256u * 8u;     // 8 wavefronts per CU
+constexpr int kConsensusBatch = 8;
 
 __global__ void se_clear2_kernel(double *out)
 {
@@ -23,48 +32,93 @@ __device__ __forceinline__ double wave_sum(double v)
     return v;
 }
 
-__global__ __launch_bounds__(256) void se_consensus_kernel(const float *__restrict__ x,
-                                                           uint64_t pitch, uint64_t ncols, int n,
-                                                           double *out)
+// x points at the first column of the range, nvec = columns / VEC, tiles = ceil(nvec / 64).
+template <int VEC, bool NT>
+__global__ __launch_bounds__(64) void se_consensus_kernel(const float *__restrict__ x,
+                                                          uint64_t pitch_bytes, uint32_t nvec,
+                                                          uint32_t tiles, int n, double *out)
 {
-    __shared__ double part[2][4];
-    double dist = 0.0, total = 0.0;
+    const uint32_t lane = threadIdx.x;
     const double inv_n = 1.0 / (double)n;
-    for (uint64_t e = (uint64_t)blockIdx.x * 256u + threadIdx.x; e < ncols;
-         e += (uint64_t)gridDim.x * 256u) {
-        double s = 0.0;
-        for (int i = 0; i < n; ++i) s += (double)x[(uint64_t)i * pitch + e];
-        const double mean = s * inv_n;
-        double d = 0.0;
-        for (int i = 0; i < n; ++i) {
-            const double t = (double)x[(uint64_t)i * pitch + e] - mean;
-            d += t * t;
+    double dist = 0.0, total = 0.0;
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        const uint32_t c = tile * 64u + lane;
+        if (c >= nvec) continue;
+        const char *col = (const char *)x + (uint64_t)c * (uint64_t)(VEC * 4);
+        const Pack<VEC> x0 = load_f32<VEC, NT>(col);
+        double s[VEC], sd[VEC], sd2[VEC];
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) { s[q] = (double)x0.a[q]; sd[q] = 0.0; sd2[q] = 0.0; }
+        for (int i = 1; i < n; i += kConsensusBatch) {
+            Pack<VEC> X[kConsensusBatch];
+#pragma unroll
+            for (int b = 0; b < kConsensusBatch; ++b)
+                if (i + b < n) X[b] = load_f32<VEC, NT>(col + (uint64_t)(i + b) * pitch_bytes);
+#pragma unroll
+            for (int b = 0; b < kConsensusBatch; ++b) {
+                if (i + b < n) {
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) {
+                        const double xi = (double)X[b].a[q];
+                        const double d = xi - (double)x0.a[q];
+                        s[q] += xi;
+                        sd[q] += d;
+                        sd2[q] = __builtin_fma(d, d, sd2[q]);
+                    }
+                }
+            }
         }
-        dist += d;
-        total += s;
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) {
+            const double dev2 = sd2[q] - sd[q] * sd[q] * inv_n;
+            dist += dev2 < 0.0 ? 0.0 : dev2;          // rounding only; NaN passes through
+            total += s[q];
+        }
     }
     dist = wave_sum(dist);
     total = wave_sum(total);
-    const int wave = (int)(threadIdx.x >> 6);
-    if ((threadIdx.x & 63u) == 0) { part[0][wave] = dist; part[1][wave] = total; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        atomicAdd(out + 0, (part[0][0] + part[0][1]) + (part[0][2] + part[0][3]));
-        atomicAdd(out + 1, (part[1][0] + part[1][1]) + (part[1][2] + part[1][3]));
+    if (lane == 0) {
+        atomicAdd(out + 0, dist);
+        atomicAdd(out + 1, total);
     }
 }
 
+template <int VEC>
+static hipError_t launch_part(const float *x, uint64_t pitch_elems, uint64_t ncols, int n,
+                              double *out_dev, hipStream_t stream)
+{
+    if (ncols == 0) return hipSuccess;
+    const uint32_t nvec = (uint32_t)(ncols / VEC);
+    const uint32_t tiles = (nvec + 63u) / 64u;
+    const uint32_t grid = tiles < kConsensusMaxGrid ? tiles : kConsensusMaxGrid;
+    // streaming loads once the rows cannot stay in the 256 MiB Infinity Cache anyway
+    const bool nt = (uint64_t)n * ncols * 4u >= ((uint64_t)192 << 20);
+    if (nt)
+        hipLaunchKernelGGL((se_consensus_kernel<VEC, true>), dim3(grid), dim3(64), 0, stream, x,
+                           pitch_elems * 4u, nvec, tiles, n, out_dev);
+    else
+        hipLaunchKernelGGL((se_consensus_kernel<VEC, false>), dim3(grid), dim3(64), 0, stream, x,
+                           pitch_elems * 4u, nvec, tiles, n, out_dev);
+    return hipGetLastError();
+}
+
+// Columns [0, ncols) of n rows of pitch_elems floats: scalar head up to 16-byte alignment,
+// 128-bit body, scalar tail; all three add into the same two doubles.
 hipError_t launch_consensus(const float *x, uint64_t pitch_elems, uint64_t ncols, int n,
                             double *out_dev, hipStream_t stream)
 {
     hipLaunchKernelGGL(se_clear2_kernel, dim3(1), dim3(1), 0, stream, out_dev);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || ncols == 0) return e;
-    uint64_t grid = (ncols + 255u) / 256u;
-    if (grid > 256u * 16u) grid = 256u * 16u;
-    hipLaunchKernelGGL(se_consensus_kernel, dim3((uint32_t)grid), dim3(256), 0, stream, x,
-                       pitch_elems, ncols, n, out_dev);
-    return hipGetLastError();
+    if (pitch_elems % 4u != 0) return launch_part<1>(x, pitch_elems, ncols, n, out_dev, stream);
+    uint64_t head = (4u - ((uintptr_t)x / 4u) % 4u) % 4u;
+    if (head > ncols) head = ncols;
+    const uint64_t body = (ncols - head) / 4u * 4u;
+    e = launch_part<1>(x, pitch_elems, head, n, out_dev, stream);
+    if (e == hipSuccess) e = launch_part<4>(x + head, pitch_elems, body, n, out_dev, stream);
+    if (e == hipSuccess)
+        e = launch_part<1>(x + head + body, pitch_elems, ncols - head - body, n, out_dev, stream);
+    return e;
 }
 
 }  // namespace se

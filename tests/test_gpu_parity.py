@@ -558,8 +558,13 @@ def test_global_average(coop):
 
 def test_consensus_diagnostics():
     out = torch.full((2,), 7.0, dtype=torch.float64, device="cuda")
-    for n, ncols in [(16, 100003), (64, 777), (3, 1), (1, 50)]:
-        case = Case(n, ncols, use_v=False, distinct_rows=True)
+    # (n, columns, pitch, element shift of the base): unaligned rows take the 32-bit path,
+    # aligned pitches the 128-bit body with scalar head and tail columns
+    for n, ncols, pitch, shift in [(16, 100003, None, 0), (64, 777, None, 0), (3, 1, None, 0),
+                                   (1, 50, None, 0), (16, 100003, 100004, 0), (16, 70001, 70004, 1),
+                                   (9, 70002, 70004, 2), (64, 33333, 33336, 3), (17, 2, 4, 3),
+                                   (4, 1024 * 300, None, 0)]:
+        case = Case(n, ncols, pitch=pitch, use_v=False, distinct_rows=True, shift=shift)
         offs = case.offsets()
         se.se_consensus(case.dx, offs, n, out)
         torch.cuda.synchronize()
