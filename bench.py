@@ -151,6 +151,26 @@ def measure_workload(name, steps, warmup, cpu_seconds, torch, se, wl):
                        "frac_of_peak": round(nbytes / per / 1e9 / HBM_PEAK_GBS, 4)},
            "se_ring_step": {"steps_per_s": round(1.0 / rper, 2), "gbs": round(nbytes / rper / 1e9, 1),
                             "frac_of_peak": round(nbytes / rper / 1e9 / HBM_PEAK_GBS, 4)}}
+    if nbytes < 1e9:
+        # launch-bound shapes: the same loop captured once in a HIP graph (K steps with their
+        # iteration numbers baked in) and replayed, which removes the per-launch host cost
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for t in range(k):
+                step_fn(x, pool[t % 2], v, offs, n, m, t, w.lr, mu, side)
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = 20
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        gper = (time.perf_counter() - t0) / (reps * k)
+        res["se_step_in_graph"] = {"steps_per_s": round(1.0 / gper, 2), "steps_per_graph": k,
+                                   "gbs": round(nbytes / gper / 1e9, 1)}
+        del graph
     del x, v, pool
     torch.cuda.empty_cache()
     if cpu_seconds > 0:
