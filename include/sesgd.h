@@ -191,7 +191,9 @@ int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
 /* Launch-shape knobs for measurement sweeps; results never depend on them.
  *   "max_blocks_per_cu"   cap on resident workgroups per compute unit, enforced by requesting
  *                         160 KiB / cap of (unused) LDS per workgroup; 0 = no cap (default 6)
- *   "nontemporal"         1 (default): streaming (non-temporal) loads and stores; 0: plain
+ *   "nontemporal"         cache policy of the row accesses: 0 plain; 1 streaming (non-temporal)
+ *                         loads and stores; 2 (default) streaming, and stores written through
+ *                         the L2 to memory at once (measured 2-4 % faster than 1)
  *   "coop_min_rows"       number of rows reduced together (group_size; n for se_ring_step and
  *                         se_global_average) from which the rows are split over the wavefronts
  *                         of a workgroup and the values to reduce are staged in LDS; below it

@@ -5,19 +5,31 @@
 
 namespace se {
 
+template <int NT>
 __global__ __launch_bounds__(64) void se_calib_copy_kernel(const f32x4 *__restrict__ src,
                                                            f32x4 *__restrict__ dst, uint64_t nvec)
 {
     const uint64_t i = (uint64_t)blockIdx.x * 64u + threadIdx.x;
-    if (i < nvec) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+    if (i >= nvec) return;
+    const f32x4 v = ld<f32x4, NT>(src + i);
+    if constexpr (NT == kStreamThrough) st_through(dst + (uint64_t)blockIdx.x * 64u, threadIdx.x * 16u, v);
+    else st<f32x4, NT>(dst + i, v);
 }
 
-hipError_t launch_calib_copy(void *dst, const void *src, uint64_t nbytes, hipStream_t stream)
+// policy: the cache policy the step kernels use (se::Policy), so that the copy is a ceiling
+// for the same kind of access
+hipError_t launch_calib_copy(void *dst, const void *src, uint64_t nbytes, int policy,
+                             hipStream_t stream)
 {
     const uint64_t nvec = nbytes / 16u;
-    const uint64_t grid = (nvec + 63u) / 64u;
-    hipLaunchKernelGGL(se_calib_copy_kernel, dim3((uint32_t)grid), dim3(64), 0, stream,
-                       (const f32x4 *)src, (f32x4 *)dst, nvec);
+    const dim3 grid((uint32_t)((nvec + 63u) / 64u));
+    const f32x4 *s = (const f32x4 *)src;
+    f32x4 *d = (f32x4 *)dst;
+    switch (policy) {
+    case kPlain: hipLaunchKernelGGL(se_calib_copy_kernel<kPlain>, grid, dim3(64), 0, stream, s, d, nvec); break;
+    case kStream: hipLaunchKernelGGL(se_calib_copy_kernel<kStream>, grid, dim3(64), 0, stream, s, d, nvec); break;
+    default: hipLaunchKernelGGL(se_calib_copy_kernel<kStreamThrough>, grid, dim3(64), 0, stream, s, d, nvec); break;
+    }
     return hipGetLastError();
 }
 

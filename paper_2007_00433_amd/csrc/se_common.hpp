@@ -36,7 +36,7 @@ struct StepArgs {
 struct LaunchShape {
     int vec;                // 4, 2 or 1 columns per lane
     bool bf16;              // gradient storage
-    bool nontemporal;       // streaming loads and stores
+    int nontemporal;        // cache policy of the row accesses (se::Policy)
     uint32_t lds_bytes;     // dynamic LDS requested only to cap resident workgroups per CU
 };
 
@@ -49,7 +49,8 @@ hipError_t launch_plan(uint64_t seed, int64_t iter, int n, int m, int32_t *group
                        int32_t *members_dev, hipStream_t stream);
 hipError_t launch_consensus(const float *x, uint64_t pitch_elems, uint64_t ncols, int n,
                             double *out_dev, hipStream_t stream);
-hipError_t launch_calib_copy(void *dst, const void *src, uint64_t nbytes, hipStream_t stream);
+hipError_t launch_calib_copy(void *dst, const void *src, uint64_t nbytes, int policy,
+                             hipStream_t stream);
 
 // Lets `kernel` request up to the whole LDS of a compute unit as dynamic shared memory; done
 // once per device (bit per device ordinal in `done`).

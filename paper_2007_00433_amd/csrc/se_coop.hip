@@ -19,7 +19,7 @@ namespace se {
 
 constexpr int kRowsPerWave = 4;
 
-template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, bool NT, int MODE>
+template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, int NT, int MODE>
 __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
 {
     extern __shared__ float staged[];          // [rows][64 lanes][VEC]
@@ -82,17 +82,17 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
                             out.a[q] = __builtin_fmaf(p.neg_lr, vn.a[q], X[r].a[q]);
                         }
                         if constexpr (HAS_V)
-                            store_f32<VEC, NT>((char *)p.v + row[r] * p.pitch_bytes + off, vn);
+                            store_f32<VEC, NT>((char *)p.v + row[r] * p.pitch_bytes, off, vn);
                     }
-                    store_f32<VEC, false>((char *)(staged + ((size_t)(first + r) * 64 + lane) * VEC), out);
+                    store_f32<VEC, kPlain>((char *)(staged + ((size_t)(first + r) * 64 + lane) * VEC), 0u, out);
                 }
             }
         }
         __syncthreads();
         if (valid) {
-            Pack<VEC> s = load_f32<VEC, false>((const char *)(staged + (size_t)lane * VEC));
+            Pack<VEC> s = load_f32<VEC, kPlain>((const char *)(staged + (size_t)lane * VEC));
             for (int r = 1; r < p.m; ++r) {
-                const Pack<VEC> t = load_f32<VEC, false>((const char *)(staged + ((size_t)r * 64 + lane) * VEC));
+                const Pack<VEC> t = load_f32<VEC, kPlain>((const char *)(staged + ((size_t)r * 64 + lane) * VEC));
 #pragma unroll
                 for (int q = 0; q < VEC; ++q) s.a[q] = s.a[q] + t.a[q];
             }
@@ -112,10 +112,10 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
                             xn.a[q] = __builtin_fmaf(p.neg_lr, vn.a[q], X[r].a[q]);
                         }
                         if constexpr (HAS_V)
-                            store_f32<VEC, NT>((char *)p.v + row[r] * p.pitch_bytes + off, vn);
-                        store_f32<VEC, NT>((char *)p.x + row[r] * p.pitch_bytes + off, xn);
+                            store_f32<VEC, NT>((char *)p.v + row[r] * p.pitch_bytes, off, vn);
+                        store_f32<VEC, NT>((char *)p.x + row[r] * p.pitch_bytes, off, xn);
                     } else {
-                        store_f32<VEC, NT>((char *)p.x + row[r] * p.pitch_bytes + off, mean);
+                        store_f32<VEC, NT>((char *)p.x + row[r] * p.pitch_bytes, off, mean);
                     }
                 }
             }
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
     }
 }
 
-template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, bool NT, int MODE>
+template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, int NT, int MODE>
 static hipError_t launch_one(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
     const int waves = (a.m + kRowsPerWave - 1) / kRowsPerWave;     // <= 16 for m <= 64
@@ -141,7 +141,7 @@ static hipError_t launch_one(const StepArgs &a, const LaunchShape &s, hipStream_
     return hipGetLastError();
 }
 
-template <int VEC, bool BF16, bool NT, int MODE>
+template <int VEC, bool BF16, int NT, int MODE>
 static hipError_t launch_flags(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
     const bool has_v = a.v != nullptr, has_wd = a.wd != 0.0f;
@@ -151,7 +151,7 @@ static hipError_t launch_flags(const StepArgs &a, const LaunchShape &s, hipStrea
                   : launch_one<VEC, BF16, false, false, NT, MODE>(a, s, stream);
 }
 
-template <int VEC, bool BF16, bool NT>
+template <int VEC, bool BF16, int NT>
 static hipError_t launch_mode(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
     switch (a.mode) {
@@ -166,8 +166,11 @@ static hipError_t launch_mode(const StepArgs &a, const LaunchShape &s, hipStream
 template <int VEC, bool BF16>
 static hipError_t launch_nt(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
-    return s.nontemporal ? launch_mode<VEC, BF16, true>(a, s, stream)
-                         : launch_mode<VEC, BF16, false>(a, s, stream);
+    switch (s.nontemporal) {
+    case kPlain: return launch_mode<VEC, BF16, kPlain>(a, s, stream);
+    case kStream: return launch_mode<VEC, BF16, kStream>(a, s, stream);
+    default: return launch_mode<VEC, BF16, kStreamThrough>(a, s, stream);
+    }
 }
 
 hipError_t launch_coop(const StepArgs &a, const LaunchShape &s, hipStream_t stream)

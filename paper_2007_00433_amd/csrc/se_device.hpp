@@ -93,19 +93,45 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 
-template <typename T, bool NT> __device__ __forceinline__ T ld(const void *p)
+// Cache policy of the row accesses: kPlain, kStream (non-temporal: the line is the first to be
+// evicted), kStreamThrough (as kStream, and stores are written through the L2 to memory at
+// once instead of waiting there as dirty lines: the `sc1` bit of the store).
+enum Policy { kPlain = 0, kStream = 1, kStreamThrough = 2 };
+
+template <typename T, int NT> __device__ __forceinline__ T ld(const void *p)
 {
-    if constexpr (NT) return __builtin_nontemporal_load((const T *)p);
+    if constexpr (NT != kPlain) return __builtin_nontemporal_load((const T *)p);
     else return *(const T *)p;
 }
-template <typename T, bool NT> __device__ __forceinline__ void st(void *p, T v)
+template <typename T, int NT> __device__ __forceinline__ void st(void *p, T v)
 {
-    if constexpr (NT) __builtin_nontemporal_store(v, (T *)p);
+    if constexpr (NT != kPlain) __builtin_nontemporal_store(v, (T *)p);
     else *(T *)p = v;
 }
 
+// Written-through streaming store of 16, 8 or 4 bytes at (wave-uniform row) + (per-lane byte
+// offset): a raw buffer store, the form whose cache-policy operand reaches the sc1 bit.  The
+// descriptor covers 4 GiB from `row` (rows are shorter), dword 3 is the plain raw-buffer
+// setting of the gfx9 family.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+constexpr int kRawBufferFlags = 0x00020000;
+constexpr int kAuxStreamThrough = (1 << 1) | (1 << 4);      // nt | sc1
+
+template <typename T> __device__ __forceinline__ void st_through(void *row, uint32_t off, T v)
+{
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(row, 0, -1, kRawBufferFlags);
+    static_assert(sizeof(T) == 16 || sizeof(T) == 8 || sizeof(T) == 4, "store width");
+    if constexpr (sizeof(T) == 16)
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rsrc, (int)off, 0, kAuxStreamThrough);
+    else if constexpr (sizeof(T) == 8)
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, v), rsrc, (int)off, 0, kAuxStreamThrough);
+    else
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), rsrc, (int)off, 0, kAuxStreamThrough);
+}
+
 // fp32 vector of N columns at byte address p
-template <int N, bool NT> __device__ __forceinline__ Pack<N> load_f32(const char *p)
+template <int N, int NT> __device__ __forceinline__ Pack<N> load_f32(const char *p)
 {
     Pack<N> r;
     if constexpr (N == 4) { f32x4 t = ld<f32x4, NT>(p); r.a[0] = t.x; r.a[1] = t.y; r.a[2] = t.z; r.a[3] = t.w; }
@@ -113,14 +139,21 @@ template <int N, bool NT> __device__ __forceinline__ Pack<N> load_f32(const char
     else { r.a[0] = ld<float, NT>(p); }
     return r;
 }
-template <int N, bool NT> __device__ __forceinline__ void store_f32(char *p, const Pack<N> &r)
+// fp32 vector of N columns to (wave-uniform row address) + (per-lane byte offset)
+template <int N, int NT> __device__ __forceinline__ void store_f32(char *row, uint32_t off, const Pack<N> &r)
 {
-    if constexpr (N == 4) { f32x4 t = {r.a[0], r.a[1], r.a[2], r.a[3]}; st<f32x4, NT>(p, t); }
-    else if constexpr (N == 2) { f32x2 t = {r.a[0], r.a[1]}; st<f32x2, NT>(p, t); }
-    else { st<float, NT>(p, r.a[0]); }
+    if constexpr (N == 4) {
+        const f32x4 t = {r.a[0], r.a[1], r.a[2], r.a[3]};
+        if constexpr (NT == kStreamThrough) st_through(row, off, t); else st<f32x4, NT>(row + off, t);
+    } else if constexpr (N == 2) {
+        const f32x2 t = {r.a[0], r.a[1]};
+        if constexpr (NT == kStreamThrough) st_through(row, off, t); else st<f32x2, NT>(row + off, t);
+    } else {
+        if constexpr (NT == kStreamThrough) st_through(row, off, r.a[0]); else st<float, NT>(row + off, r.a[0]);
+    }
 }
 // bf16 vector of N columns at byte address p, widened to fp32 (exact: bits << 16)
-template <int N, bool NT> __device__ __forceinline__ Pack<N> load_bf16(const char *p)
+template <int N, int NT> __device__ __forceinline__ Pack<N> load_bf16(const char *p)
 {
     Pack<N> r;
     if constexpr (N == 4) {
@@ -135,7 +168,7 @@ template <int N, bool NT> __device__ __forceinline__ Pack<N> load_bf16(const cha
     }
     return r;
 }
-template <int N, bool BF16, bool NT> __device__ __forceinline__ Pack<N> load_grad(const char *p)
+template <int N, bool BF16, int NT> __device__ __forceinline__ Pack<N> load_grad(const char *p)
 {
     if constexpr (BF16) return load_bf16<N, NT>(p);
     else return load_f32<N, NT>(p);

@@ -23,7 +23,7 @@
 namespace se {
 
 // ---- kSesgd: B members at once -------------------------------------------------------------
-template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, bool NT, int B, bool FIRST>
+template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, int NT, int B, bool FIRST>
 __device__ __forceinline__ void sesgd_batch(const StepArgs &p, uint64_t &todo, uint32_t off,
                                             uint32_t goff, uint64_t gpitch_bytes, Pack<VEC> &s)
 {
@@ -49,12 +49,12 @@ __device__ __forceinline__ void sesgd_batch(const StepArgs &p, uint64_t &todo, u
             s.a[c] = (FIRST && b == 0) ? xhat : s.a[c] + xhat;
         }
         if constexpr (HAS_V)
-            store_f32<VEC, NT>((char *)p.v + row[b] * p.pitch_bytes + off, vn);
+            store_f32<VEC, NT>((char *)p.v + row[b] * p.pitch_bytes, off, vn);
     }
 }
 
 // ---- kGradAvg / kAvgOnly, pass 1: sum one array over B members ---------------------------------
-template <int VEC, bool BF16, bool NT, bool PARAMS, int B, bool FIRST>
+template <int VEC, bool BF16, int NT, bool PARAMS, int B, bool FIRST>
 __device__ __forceinline__ void sum_batch(const StepArgs &p, uint64_t &todo, uint32_t off,
                                           uint64_t pitch_bytes, Pack<VEC> &s)
 {
@@ -75,7 +75,7 @@ __device__ __forceinline__ void sum_batch(const StepArgs &p, uint64_t &todo, uin
 }
 
 // ---- kGradAvg, pass 2: every member updates with the group's mean gradient ---------------------
-template <int VEC, bool HAS_V, bool HAS_WD, bool NT, int B, bool FIRST>
+template <int VEC, bool HAS_V, bool HAS_WD, int NT, int B, bool FIRST>
 __device__ __forceinline__ void update_batch(const StepArgs &p, uint64_t &todo, uint32_t off,
                                              const Pack<VEC> &gbar)
 {
@@ -99,8 +99,8 @@ __device__ __forceinline__ void update_batch(const StepArgs &p, uint64_t &todo, 
             xn.a[c] = __builtin_fmaf(p.neg_lr, vn.a[c], X[b].a[c]);
         }
         if constexpr (HAS_V)
-            store_f32<VEC, NT>((char *)p.v + row[b] * p.pitch_bytes + off, vn);
-        store_f32<VEC, NT>((char *)p.x + row[b] * p.pitch_bytes + off, xn);
+            store_f32<VEC, NT>((char *)p.v + row[b] * p.pitch_bytes, off, vn);
+        store_f32<VEC, NT>((char *)p.x + row[b] * p.pitch_bytes, off, xn);
     }
 }
 
@@ -122,7 +122,7 @@ __device__ __forceinline__ void update_batch(const StepArgs &p, uint64_t &todo, 
             if (first_) { CALL(1, true); } else { CALL(1, false); } } }                    \
     } while (0)
 
-template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, bool NT, int MODE, int BMAX>
+template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, int NT, int MODE, int BMAX>
 __global__ __launch_bounds__(64) void se_step_kernel(const StepArgs p)
 {
     const int lane = (int)threadIdx.x;
@@ -168,11 +168,11 @@ __global__ __launch_bounds__(64) void se_step_kernel(const StepArgs p)
 #undef SE_CALL
     } else {
         while (todo)
-            store_f32<VEC, NT>((char *)p.x + next_row(todo) * p.pitch_bytes + off, mean);
+            store_f32<VEC, NT>((char *)p.x + next_row(todo) * p.pitch_bytes, off, mean);
     }
 }
 
-template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, bool NT, int MODE, int BMAX>
+template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, int NT, int MODE, int BMAX>
 static hipError_t launch_one(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
     auto kern = se_step_kernel<VEC, BF16, HAS_V, HAS_WD, NT, MODE, BMAX>;
@@ -186,7 +186,7 @@ static hipError_t launch_one(const StepArgs &a, const LaunchShape &s, hipStream_
     return hipGetLastError();
 }
 
-template <int VEC, bool BF16, bool NT, int MODE, int BMAX>
+template <int VEC, bool BF16, int NT, int MODE, int BMAX>
 static hipError_t launch_flags(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
     const bool has_v = a.v != nullptr, has_wd = a.wd != 0.0f;
@@ -196,7 +196,7 @@ static hipError_t launch_flags(const StepArgs &a, const LaunchShape &s, hipStrea
                   : launch_one<VEC, BF16, false, false, NT, MODE, BMAX>(a, s, stream);
 }
 
-template <int VEC, bool BF16, bool NT>
+template <int VEC, bool BF16, int NT>
 static hipError_t launch_mode(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
     switch (a.mode) {
@@ -215,8 +215,11 @@ static hipError_t launch_mode(const StepArgs &a, const LaunchShape &s, hipStream
 template <int VEC, bool BF16>
 static hipError_t launch_nt(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
-    return s.nontemporal ? launch_mode<VEC, BF16, true>(a, s, stream)
-                         : launch_mode<VEC, BF16, false>(a, s, stream);
+    switch (s.nontemporal) {
+    case kPlain: return launch_mode<VEC, BF16, kPlain>(a, s, stream);
+    case kStream: return launch_mode<VEC, BF16, kStream>(a, s, stream);
+    default: return launch_mode<VEC, BF16, kStreamThrough>(a, s, stream);
+    }
 }
 
 hipError_t launch_step(const StepArgs &a, const LaunchShape &s, hipStream_t stream)

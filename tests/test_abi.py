@@ -52,7 +52,7 @@ def test_seed_and_tuning_state():
     assert se.se_get_seed() == 12345678901234567890
     se.se_set_seed(0)
     assert len(se.TUNING_KNOBS) == 5
-    for name, good, bad in (("nontemporal", 0, 2),
+    for name, good, bad in (("nontemporal", 0, 3),
                             ("max_blocks_per_cu", 2, 33), ("coop_min_rows", 4, 66),
                             ("cache_resident_mib", 0, -1), ("coop_tiles", 3, -1)):
         assert name in se.TUNING_KNOBS

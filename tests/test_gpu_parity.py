@@ -221,6 +221,39 @@ def test_misaligned_base_addresses(shift, dtype):
     case.check(f"ring shift {shift} {dtype}")
 
 
+@pytest.fixture
+def always_streaming():
+    """Small buffers normally take the cache-resident path (plain accesses); this forces the
+    streaming path the full-size launches use."""
+    old = {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}
+    se.se_set_tuning("cache_resident_mib", 0)
+    yield
+    for k, val in old.items():
+        se.se_set_tuning(k, val)
+
+
+@pytest.mark.parametrize("policy", [1, 2])
+@pytest.mark.parametrize("coop_min_rows", [0, 1])
+def test_streaming_policies_on_every_access_width(policy, coop_min_rows, always_streaming):
+    """Streaming loads/stores (policy 1) and written-through streaming stores (policy 2) in
+    their 128-, 64- and 32-bit forms, fp32 and bf16 gradients, both kernel forms, all modes."""
+    se.se_set_tuning("nontemporal", policy)
+    se.se_set_tuning("coop_min_rows", coop_min_rows)
+    for ncols, shift in [(1028, 0), (1030, 0), (1031, 0), (1536, 1), (1536, 2), (777, 4)]:
+        for dtype in ("f32", "bf16"):
+            what = f"policy {policy} coop {coop_min_rows} cols {ncols} shift {shift} {dtype}"
+            say(what)
+            case = Case(8, ncols, dtype=dtype, shift=shift, distinct_rows=True, v_std=0.01)
+            run_sesgd(case, 4, 2, 0.1, 0.9, 1e-2)
+            case.check(what)
+            run_ring(case, 2, 0.1, 0.9, 1e-2)
+            case.check(what + " ring")
+        case = Case(8, ncols, use_v=False, shift=shift, distinct_rows=True)
+        se.se_global_average(case.dx, case.offsets(), 8)
+        oracle.global_average(case.hx)
+        case.check(what + " global average")
+
+
 @pytest.mark.parametrize("n,ms", [(64, [1, 2, 4, 8, 16, 32, 64]), (12, [1, 2, 3, 4, 6, 12]),
                                   (63, [7, 9, 21]), (5, [1, 5]), (1, [1]), (30, [15, 10])])
 def test_group_sizes(n, ms):
@@ -312,6 +345,7 @@ def test_results_do_not_depend_on_launch_knobs_or_stream():
               dict(coop_min_rows=0), dict(coop_min_rows=1), dict(coop_min_rows=2, max_blocks_per_cu=3),
               dict(coop_min_rows=16, nontemporal=0),
               dict(cache_resident_mib=0), dict(cache_resident_mib=0, coop_min_rows=1, max_blocks_per_cu=2),
+              dict(cache_resident_mib=0, nontemporal=1), dict(cache_resident_mib=0, nontemporal=1, coop_min_rows=1),
               dict(coop_min_rows=1, coop_tiles=1), dict(coop_min_rows=1, coop_tiles=7),
               dict(coop_min_rows=1, coop_tiles=4096)]
     defaults = {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}
@@ -680,7 +714,7 @@ def test_randomised_configurations():
         wd = float(rng.choice([0.0, 1e-4, 5e-4]))
         flags = GA if rng.integers(0, 3) == 0 else 0
         shift = int(rng.choice([0, 0, 1, 2, 4]))
-        knobs = dict(coop_min_rows=int(rng.choice([0, 1, 8, 16])), nontemporal=int(rng.integers(0, 2)),
+        knobs = dict(coop_min_rows=int(rng.choice([0, 1, 8, 16])), nontemporal=int(rng.integers(0, 3)),
                      coop_tiles=int(rng.choice([1, 2, 4, 5, 64])),
                      max_blocks_per_cu=int(rng.choice([0, 1, 6, 32])), cache_resident_mib=int(rng.choice([0, 192])))
         for k, val in {**defaults, **knobs}.items():
