@@ -190,7 +190,8 @@ int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
 
 /* Launch-shape knobs for measurement sweeps; results never depend on them.
  *   "max_blocks_per_cu"   cap on resident workgroups per compute unit, enforced by requesting
- *                         160 KiB / cap of (unused) LDS per workgroup; 0 = no cap (default 6)
+ *                         160 KiB / cap of (unused) LDS per workgroup; 0 = no cap (default 6; the
+ *                         cooperative form of the SESGD update takes two more)
  *   "nontemporal"         cache policy of the row accesses: 0 plain; 1 streaming (non-temporal)
  *                         loads and stores; 2 (default) streaming, and stores written through
  *                         the L2 to memory at once (measured 2-4 % faster than 1)
