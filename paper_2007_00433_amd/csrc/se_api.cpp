@@ -101,7 +101,7 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     const uint64_t per_elem = 8u + (uint64_t)j.grad_bytes + (j.v ? 8u : 0u);
     const uint64_t moved = (uint64_t)j.n * (uint64_t)(c1 - c0) * per_elem;
     const bool streams = moved >= ((uint64_t)g_cache_resident_mib.load() << 20);
-    s.nontemporal = streams ? g_nontemporal.load() : 0;
+    s.policy = streams ? g_nontemporal.load() : se::kPlain;
     int cap = streams ? g_max_blocks_per_cu.load() : 0;
     const int coop = g_coop_min_rows.load();
     const bool use_coop = coop > 0 && j.m >= coop;

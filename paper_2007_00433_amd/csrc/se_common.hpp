@@ -33,10 +33,15 @@ struct StepArgs {
     int mode;                  // Mode
 };
 
+// Cache policy of the row accesses: kPlain, kStream (non-temporal: the line is the first to be
+// evicted), kStreamThrough (as kStream, and stores are written through the L2 to memory at
+// once instead of waiting there as dirty lines: the `sc1` bit of the store).
+enum Policy { kPlain = 0, kStream = 1, kStreamThrough = 2 };
+
 struct LaunchShape {
     int vec;                // 4, 2 or 1 columns per lane
     bool bf16;              // gradient storage
-    int nontemporal;        // cache policy of the row accesses (se::Policy)
+    int policy;             // Policy of the row accesses
     uint32_t lds_bytes;     // dynamic LDS requested only to cap resident workgroups per CU
 };
 

@@ -93,11 +93,6 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 
-// Cache policy of the row accesses: kPlain, kStream (non-temporal: the line is the first to be
-// evicted), kStreamThrough (as kStream, and stores are written through the L2 to memory at
-// once instead of waiting there as dirty lines: the `sc1` bit of the store).
-enum Policy { kPlain = 0, kStream = 1, kStreamThrough = 2 };
-
 template <typename T, int NT> __device__ __forceinline__ T ld(const void *p)
 {
     if constexpr (NT != kPlain) return __builtin_nontemporal_load((const T *)p);

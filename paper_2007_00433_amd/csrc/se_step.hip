@@ -215,7 +215,7 @@ static hipError_t launch_mode(const StepArgs &a, const LaunchShape &s, hipStream
 template <int VEC, bool BF16>
 static hipError_t launch_nt(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
-    switch (s.nontemporal) {
+    switch (s.policy) {
     case kPlain: return launch_mode<VEC, BF16, kPlain>(a, s, stream);
     case kStream: return launch_mode<VEC, BF16, kStream>(a, s, stream);
     default: return launch_mode<VEC, BF16, kStreamThrough>(a, s, stream);
