@@ -190,15 +190,19 @@ int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
 
 /* Launch-shape knobs for measurement sweeps; results never depend on them.
  *   "max_blocks_per_cu"   cap on resident workgroups per compute unit, enforced by requesting
- *                         160 KiB / cap of (unused) LDS per workgroup; 0 = no cap (default 6; the
- *                         cooperative form of the SESGD update takes two more)
+ *                         160 KiB / cap of (unused) LDS per workgroup; 0 = no cap; -1 (default) =
+ *                         the measured optimum per launch: 16, 12, 6 for group sizes 1, 2, 4
+ *                         (about 72 KiB of loads in flight per compute unit), 4 up to 8 rows, 2
+ *                         beyond, 4 for the ring and the global average, 6 for the staged form
+ *                         (which takes two more for the SESGD update, also when the cap is given
+ *                         explicitly)
  *   "nontemporal"         cache policy of the row accesses: 0 plain; 1 streaming (non-temporal)
  *                         loads and stores; 2 (default) streaming, and stores written through
  *                         the L2 to memory at once (measured 2-4 % faster than 1)
- *   "coop_min_rows"       number of rows reduced together (group_size; n for se_ring_step and
- *                         se_global_average) from which the rows are split over the wavefronts
- *                         of a workgroup and the values to reduce are staged in LDS; below it
- *                         one wavefront owns all rows of its group.  0 = never (default 8)
+ *   "cooperative"         1: the rows reduced together are split over the wavefronts of a
+ *                         workgroup and the values to reduce are staged in LDS; 0: one wavefront
+ *                         owns all rows of its group; -1 (default): the staged form where it
+ *                         measured faster (the SESGD update with 8 to 15 rows per group)
  *   "coop_tiles"          cooperative form: consecutive 64-lane tiles one workgroup walks through;
  *                         0 = chosen by group size: 4 above 32 rows, else 1 (default 0)
  *   "cache_resident_mib"  a launch that moves fewer MiB than this (default 192; the Infinity

@@ -32,7 +32,7 @@ EXPORTS = ("se_plan", "se_plan_device", "se_step", "se_step_bf16g", "se_ring_ste
 
 
 SE_FLAG_GRAD_AVG = 1
-TUNING_KNOBS = ("max_blocks_per_cu", "nontemporal", "coop_min_rows", "coop_tiles",
+TUNING_KNOBS = ("max_blocks_per_cu", "nontemporal", "cooperative", "coop_tiles",
                 "cache_resident_mib")
 
 

@@ -14,8 +14,8 @@ namespace {
 
 std::atomic<uint64_t> g_seed{0};
 std::atomic<int> g_nontemporal{2};         // se::Policy of the row accesses of launches that stream from HBM
-std::atomic<int> g_max_blocks_per_cu{6};  // resident workgroups per CU (0 = no cap)
-std::atomic<int> g_coop_min_rows{8};      // rows reduced together from which the LDS form is used (0 = never)
+std::atomic<int> g_max_blocks_per_cu{-1}; // resident workgroups per CU (0 = no cap, -1 = chosen per launch)
+std::atomic<int> g_cooperative{-1};       // LDS-staged form: 0 never, 1 always, -1 where it measured faster
 std::atomic<int> g_coop_tiles{0};         // cooperative form: consecutive tiles per workgroup (0 = by group size)
 std::atomic<int> g_cache_resident_mib{192};  // launches moving fewer MiB stay in the 256 MiB Infinity Cache
 
@@ -73,6 +73,22 @@ struct Job {
     hipStream_t stream;
 };
 
+// Resident single-wavefront workgroups per CU, from sweeps on MI355X (fp32 and bf16 gradients,
+// n = 16, 32, 64).  Up to 4 rows per group all loads of a tile are issued at once and about
+// 72 KiB in flight per CU is the optimum: 6 workgroups for the headline shape (4 members x 3
+// arrays x 1 KiB per wavefront), 12 for groups of 2, 16 for group_size 1.  Larger groups are
+// walked in batches of 8 rows: 4 workgroups up to 8 rows, 2 beyond, 4 for the two-pass modes.
+// Fewer starve the memory system, more scatter the tiles in flight and lose DRAM locality.
+int auto_blocks_per_cu(const Job &j, int vec)
+{
+    if (j.mode != se::kSesgd) return 4;
+    if (j.m > 8) return 2;
+    if (j.m > 4) return 4;
+    const int in_flight = j.m * 64 * vec * (4 + j.grad_bytes + (j.v ? 4 : 0));   // bytes per wavefront
+    const int cap = 72 * 1024 / in_flight;
+    return cap < 4 ? 4 : cap > 16 ? 16 : cap;
+}
+
 // One launch over columns [c0, c1) with `vec` columns per lane; (c1 - c0) % vec == 0 and every
 // row of every buffer is vec-aligned at column c0.
 hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
@@ -102,9 +118,12 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     const uint64_t moved = (uint64_t)j.n * (uint64_t)(c1 - c0) * per_elem;
     const bool streams = moved >= ((uint64_t)g_cache_resident_mib.load() << 20);
     s.policy = streams ? g_nontemporal.load() : se::kPlain;
+    // The LDS-staged form measured 1-3 % faster for the SESGD update with 8 to 15 rows per
+    // group and slower or equal everywhere else (larger groups, the ring, the global average).
+    const int coop = g_cooperative.load();
+    const bool use_coop = coop > 0 || (coop < 0 && j.mode == se::kSesgd && j.m >= 8 && j.m < 16);
     int cap = streams ? g_max_blocks_per_cu.load() : 0;
-    const int coop = g_coop_min_rows.load();
-    const bool use_coop = coop > 0 && j.m >= coop;
+    if (cap < 0) cap = use_coop ? 6 : auto_blocks_per_cu(j, vec);
     // the cooperative SESGD update measured 1-3 % faster with two more resident workgroups
     if (use_coop && j.mode == se::kSesgd && cap > 0) cap += 2;
     s.lds_bytes = cap > 0 ? (se::kLdsPerCu / (uint32_t)cap) & ~1023u : 0u;
@@ -164,9 +183,9 @@ int plan_check(int n, int group_size, int64_t iter, const void *group_of)
 
 struct Knob { const char *name; std::atomic<int> *value; int lo, hi; };
 Knob kKnobs[] = {
-    {"max_blocks_per_cu", &g_max_blocks_per_cu, 0, 32},
+    {"max_blocks_per_cu", &g_max_blocks_per_cu, -1, 32},
     {"nontemporal", &g_nontemporal, 0, 2},
-    {"coop_min_rows", &g_coop_min_rows, 0, 65},
+    {"cooperative", &g_cooperative, -1, 1},
     {"coop_tiles", &g_coop_tiles, 0, 4096},
     {"cache_resident_mib", &g_cache_resident_mib, 0, 1 << 20},
 };

@@ -102,7 +102,7 @@ int main()
         EXPECT(g_recs.size() == from + 1 && g_recs[from].vec == 4 && !g_recs[from].coop &&
                g_recs[from].tiles == (25557056u / 4 + 63) / 64);
         EXPECT(se_ring_step((float *)X, (const float *)G, (float *)V, offs, 1, 16, 0.1f, 0.9f, nullptr) == SE_OK);
-        EXPECT(g_recs.back().coop && g_recs.back().mode == se::kGradAvg && g_recs.back().m == 16 && g_recs.back().k == 1);
+        EXPECT(!g_recs.back().coop && g_recs.back().mode == se::kGradAvg && g_recs.back().m == 16 && g_recs.back().k == 1);
     }
     // error paths write nothing and launch nothing
     {

@@ -53,7 +53,7 @@ def test_seed_and_tuning_state():
     se.se_set_seed(0)
     assert len(se.TUNING_KNOBS) == 5
     for name, good, bad in (("nontemporal", 0, 3),
-                            ("max_blocks_per_cu", 2, 33), ("coop_min_rows", 4, 66),
+                            ("max_blocks_per_cu", 2, 33), ("cooperative", 1, 2),
                             ("cache_resident_mib", 0, -1), ("coop_tiles", 3, -1)):
         assert name in se.TUNING_KNOBS
         old = se.se_get_tuning(name)

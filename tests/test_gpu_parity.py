@@ -233,15 +233,15 @@ def always_streaming():
 
 
 @pytest.mark.parametrize("policy", [1, 2])
-@pytest.mark.parametrize("coop_min_rows", [0, 1])
-def test_streaming_policies_on_every_access_width(policy, coop_min_rows, always_streaming):
+@pytest.mark.parametrize("cooperative", [0, 1])
+def test_streaming_policies_on_every_access_width(policy, cooperative, always_streaming):
     """Streaming loads/stores (policy 1) and written-through streaming stores (policy 2) in
     their 128-, 64- and 32-bit forms, fp32 and bf16 gradients, both kernel forms, all modes."""
     se.se_set_tuning("nontemporal", policy)
-    se.se_set_tuning("coop_min_rows", coop_min_rows)
+    se.se_set_tuning("cooperative", cooperative)
     for ncols, shift in [(1028, 0), (1030, 0), (1031, 0), (1536, 1), (1536, 2), (777, 4)]:
         for dtype in ("f32", "bf16"):
-            what = f"policy {policy} coop {coop_min_rows} cols {ncols} shift {shift} {dtype}"
+            what = f"policy {policy} coop {cooperative} cols {ncols} shift {shift} {dtype}"
             say(what)
             case = Case(8, ncols, dtype=dtype, shift=shift, distinct_rows=True, v_std=0.01)
             run_sesgd(case, 4, 2, 0.1, 0.9, 1e-2)
@@ -342,12 +342,14 @@ def test_results_do_not_depend_on_launch_knobs_or_stream():
     stream = torch.cuda.Stream()
     shapes = [dict(), dict(max_blocks_per_cu=0, nontemporal=0),
               dict(max_blocks_per_cu=4), dict(max_blocks_per_cu=1), dict(max_blocks_per_cu=32),
-              dict(coop_min_rows=0), dict(coop_min_rows=1), dict(coop_min_rows=2, max_blocks_per_cu=3),
-              dict(coop_min_rows=16, nontemporal=0),
-              dict(cache_resident_mib=0), dict(cache_resident_mib=0, coop_min_rows=1, max_blocks_per_cu=2),
-              dict(cache_resident_mib=0, nontemporal=1), dict(cache_resident_mib=0, nontemporal=1, coop_min_rows=1),
-              dict(coop_min_rows=1, coop_tiles=1), dict(coop_min_rows=1, coop_tiles=7),
-              dict(coop_min_rows=1, coop_tiles=4096)]
+              dict(max_blocks_per_cu=6), dict(max_blocks_per_cu=16),
+              dict(cooperative=0), dict(cooperative=1), dict(cooperative=1, max_blocks_per_cu=3),
+              dict(cooperative=0, nontemporal=0),
+              dict(cache_resident_mib=0), dict(cache_resident_mib=0, cooperative=1, max_blocks_per_cu=2),
+              dict(cache_resident_mib=0, cooperative=0),
+              dict(cache_resident_mib=0, nontemporal=1), dict(cache_resident_mib=0, nontemporal=1, cooperative=1),
+              dict(cooperative=1, coop_tiles=1), dict(cooperative=1, coop_tiles=7),
+              dict(cooperative=1, coop_tiles=4096)]
     defaults = {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}
     for q, shape in enumerate(shapes):
         for k, val in {**defaults, **shape}.items():
@@ -377,9 +379,9 @@ def test_results_do_not_depend_on_launch_knobs_or_stream():
 
 @pytest.mark.parametrize("coop", [0, 1])
 def test_both_kernel_forms_for_every_group_size(coop):
-    """Single-wavefront form (coop_min_rows=0) and LDS-staged form (coop_min_rows=1) of the
+    """Single-wavefront form (cooperative=0) and LDS-staged form (cooperative=1) of the
     step and of the ring baseline, each against the oracle, over ragged widths."""
-    se.se_set_tuning("coop_min_rows", coop)
+    se.se_set_tuning("cooperative", coop)
     for n, m, ncols, dtype in [(64, 64, 777, "f32"), (64, 16, 1030, "bf16"), (24, 6, 515, "f32"),
                                (9, 3, 64, "f32"), (5, 5, 4, "bf16"), (2, 1, 258, "f32"),
                                (36, 18, 1, "f32"), (13, 13, 130, "f32")]:
@@ -520,9 +522,9 @@ def test_full_size_bert_base_full_group_sampled():
 GA = se.SE_FLAG_GRAD_AVG
 
 
-@pytest.mark.parametrize("coop", [0, 1, 8])
+@pytest.mark.parametrize("coop", [0, 1, -1])
 def test_step_ex_weight_decay_and_gradient_averaging(coop):
-    se.se_set_tuning("coop_min_rows", coop)
+    se.se_set_tuning("cooperative", coop)
     for n, m, ncols, dtype, wd, flags in [(16, 4, 1029, "f32", 5e-4, 0), (16, 4, 1029, "f32", 1e-4, GA),
                                           (64, 8, 770, "bf16", 5e-4, 0), (64, 16, 514, "bf16", 0.0, GA),
                                           (12, 3, 63, "f32", 5e-4, GA), (8, 8, 260, "f32", 1e-4, GA),
@@ -582,7 +584,7 @@ def test_local_sesgd_schedule():
 
 @pytest.mark.parametrize("coop", [0, 1])
 def test_global_average(coop):
-    se.se_set_tuning("coop_min_rows", coop)
+    se.se_set_tuning("cooperative", coop)
     for n, ncols, shift in [(16, 1027, 0), (64, 300, 0), (7, 64, 1), (1, 10, 0), (33, 2, 2)]:
         case = Case(n, ncols, use_v=False, distinct_rows=True, shift=shift)
         se.se_global_average(case.dx, case.offsets(), n)
@@ -714,9 +716,9 @@ def test_randomised_configurations():
         wd = float(rng.choice([0.0, 1e-4, 5e-4]))
         flags = GA if rng.integers(0, 3) == 0 else 0
         shift = int(rng.choice([0, 0, 1, 2, 4]))
-        knobs = dict(coop_min_rows=int(rng.choice([0, 1, 8, 16])), nontemporal=int(rng.integers(0, 3)),
+        knobs = dict(cooperative=int(rng.choice([-1, 0, 1])), nontemporal=int(rng.integers(0, 3)),
                      coop_tiles=int(rng.choice([1, 2, 4, 5, 64])),
-                     max_blocks_per_cu=int(rng.choice([0, 1, 6, 32])), cache_resident_mib=int(rng.choice([0, 192])))
+                     max_blocks_per_cu=int(rng.choice([-1, 0, 1, 6, 32])), cache_resident_mib=int(rng.choice([0, 192])))
         for k, val in {**defaults, **knobs}.items():
             se.se_set_tuning(k, val)
         se.se_set_seed(int(rng.integers(0, 2 ** 63)))
