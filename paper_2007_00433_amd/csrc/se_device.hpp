@@ -73,6 +73,10 @@ __device__ __forceinline__ uint32_t wave_group_of(uint64_t seed, int64_t iter, i
 __device__ __forceinline__ uint64_t wave_members(uint64_t seed, int64_t iter, int n, int m,
                                                  uint32_t g, int lane)
 {
+    // Two partitions need no ranking: one group of everybody, and singleton groups, where the
+    // result does not depend on which worker is called group g (each is processed once).
+    if (m == n) return n == 64 ? ~0ull : (1ull << n) - 1ull;
+    if (m == 1) return 1ull << g;
     const uint32_t rank = wave_rank(seed, iter, n, lane);
     return __ballot(lane < n && rank - g * (uint32_t)m < (uint32_t)m);
 }
