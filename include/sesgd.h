@@ -205,9 +205,10 @@ int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
  *                         measured faster (the SESGD update with 8 to 15 rows per group)
  *   "coop_tiles"          cooperative form: consecutive 64-lane tiles one workgroup walks through;
  *                         0 = chosen by group size: 4 above 32 rows, else 1 (default 0)
- *   "cache_resident_mib"  a launch that moves fewer MiB than this (default 192; the Infinity
- *                         Cache holds 256 MiB) uses plain accesses and no residency cap, which
- *                         is faster when nothing streams from HBM; 0 = always stream
+ *   "cache_resident_mib"  when a full-range call would move fewer MiB than this (default 192;
+ *                         the Infinity Cache holds 256 MiB) launches use plain accesses and no
+ *                         residency cap, which is faster when nothing streams from HBM;
+ *                         0 = always stream
  * Returns SE_ERR_ARG for an unknown name or a value out of range. */
 int se_set_tuning(const char *name, int value);
 int se_get_tuning(const char *name);

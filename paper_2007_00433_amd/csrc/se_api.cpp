@@ -112,10 +112,12 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     se::LaunchShape s;
     s.vec = vec;
     s.bf16 = j.grad_bytes == 2;
-    // Streaming accesses and a residency cap pay off when the launch streams from HBM; a launch
-    // whose whole traffic fits the Infinity Cache is faster with plain accesses and no cap.
+    // Streaming accesses and a residency cap pay off when the buffers stream from HBM; buffers
+    // that fit the Infinity Cache as a whole are faster with plain accesses and no cap.  The
+    // whole rows count, not the columns of this launch: a caller that steps layer by layer
+    // still walks through all of them between two visits of the same layer.
     const uint64_t per_elem = 8u + (uint64_t)j.grad_bytes + (j.v ? 8u : 0u);
-    const uint64_t moved = (uint64_t)j.n * (uint64_t)(c1 - c0) * per_elem;
+    const uint64_t moved = (uint64_t)j.n * (uint64_t)j.pitch * per_elem;
     const bool streams = moved >= ((uint64_t)g_cache_resident_mib.load() << 20);
     s.policy = streams ? g_nontemporal.load() : se::kPlain;
     // The LDS-staged form measured 1-3 % faster for the SESGD update with 8 to 15 rows per
