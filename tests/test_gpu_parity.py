@@ -703,11 +703,11 @@ def test_maximum_row_length_sampled():
 
 
 def test_randomised_configurations():
-    """Sixty seeded random combinations of worker count, group size, width, gradient storage,
+    """150 seeded random combinations of worker count, group size, width, gradient storage,
     momentum buffer, weight decay, mode, base-address shift, layer range and launch knobs."""
     rng = np.random.default_rng(2007_00433)
     defaults = {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}
-    for case_no in range(60):
+    for case_no in range(150):
         n = int(rng.integers(1, 65))
         m = int(rng.choice(divisors(n)))
         ncols = int(rng.choice([1, 3, 17, 64, 255, 256, 300, 1025, 4100]))
