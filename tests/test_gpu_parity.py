@@ -447,13 +447,13 @@ def test_error_codes_on_the_device_box():
 
 
 # ------------------------------------------------------------------------ full size, sampled
-def _full_size_sampled(name, iters, ring=False):
+def _full_size_sampled(name, iters, ring=False, group_size=None):
     """The benchmark's launch configuration at the workload's full size.  Inputs are drawn on
     the device by torch (seeded); the oracle replays the sampled columns exactly, because
     columns are independent.  Also checks the any-size properties: members of a group end
     bit-identical, and untouched padding stays zero."""
     w = wl.WORKLOADS[name]
-    n, m, P = w.n, w.group_size, w.P
+    n, m, P = w.n, group_size or w.group_size, w.P
     pitch = se.se_pitch(P)
     offs = w.layer_offsets(pitch)
     bf16 = w.grad_dtype == "bf16"
@@ -516,6 +516,16 @@ def test_full_size_bert_base_sampled():
 
 def test_full_size_bert_base_full_group_sampled():
     _full_size_sampled("bert_base_full", 2)
+
+
+def test_full_size_bert_base_ring_sampled():
+    _full_size_sampled("bert_base", 2, ring=True)
+
+
+@pytest.mark.parametrize("group_size", [1, 2, 16])
+def test_full_size_resnet50_other_group_sizes_sampled(group_size):
+    """The residency of the launch is chosen per group size; each choice at full size."""
+    _full_size_sampled("resnet50", 2, group_size=group_size)
 
 
 # ------------------------------------------------------------------------ extended calls
