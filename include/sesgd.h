@@ -193,7 +193,8 @@ int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
  *                         160 KiB / cap of (unused) LDS per workgroup; 0 = no cap; -1 (default) =
  *                         the measured optimum per launch: 16, 12, 6 for group sizes 1, 2, 4
  *                         (about 72 KiB of loads in flight per compute unit), 4 up to 8 rows, 2
- *                         beyond, 4 for the ring and the global average, 6 for the staged form
+ *                         beyond, 2 for the ring, 4 for the global average, 6 for the staged
+ *                         form
  *                         (which takes two more for the SESGD update, also when the cap is given
  *                         explicitly)
  *   "nontemporal"         cache policy of the row accesses: 0 plain; 1 streaming (non-temporal)

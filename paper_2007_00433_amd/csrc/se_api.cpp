@@ -77,11 +77,13 @@ struct Job {
 // n = 16, 32, 64).  Up to 4 rows per group all loads of a tile are issued at once and about
 // 72 KiB in flight per CU is the optimum: 6 workgroups for the headline shape (4 members x 3
 // arrays x 1 KiB per wavefront), 12 for groups of 2, 16 for group_size 1.  Larger groups are
-// walked in batches of 8 rows: 4 workgroups up to 8 rows, 2 beyond, 4 for the two-pass modes.
+// walked in batches of 8 rows: 4 workgroups up to 8 rows, 2 beyond; gradient averaging (the
+// ring) 2; parameter averaging 4.
 // Fewer starve the memory system, more scatter the tiles in flight and lose DRAM locality.
 int auto_blocks_per_cu(const Job &j, int vec)
 {
-    if (j.mode != se::kSesgd) return 4;
+    if (j.mode == se::kGradAvg) return 2;
+    if (j.mode == se::kAvgOnly) return 4;
     if (j.m > 8) return 2;
     if (j.m > 4) return 4;
     const int in_flight = j.m * 64 * vec * (4 + j.grad_bytes + (j.v ? 4 : 0));   // bytes per wavefront

@@ -164,7 +164,7 @@ __global__ __launch_bounds__(64) void se_step_kernel(const StepArgs p)
     todo = members;
     if constexpr (MODE == kGradAvg) {
 #define SE_CALL(B, F) update_batch<VEC, HAS_V, HAS_WD, NT, B, F>(p, todo, off, mean)
-        SE_FOR_MEMBER_BATCHES(4, p.m, SE_CALL);
+        SE_FOR_MEMBER_BATCHES(8, p.m, SE_CALL);
 #undef SE_CALL
     } else {
         while (todo)
