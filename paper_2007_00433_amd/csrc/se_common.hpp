@@ -25,7 +25,8 @@ struct StepArgs {
     uint64_t seed;
     int64_t iter;
     uint64_t pitch_bytes;      // row distance of x and v in bytes (half of it for bf16 g)
-    uint32_t nvec;
+    uint32_t lead;             // lane-columns at the start of the launch that are not touched (< 64)
+    uint32_t nvec;             // lane-columns of the launch, the leading ones included
     uint32_t tiles;
     uint32_t coop_tiles;       // cooperative form: consecutive tiles one workgroup walks through
     int n, m, k;               // workers, rows reduced together, groups

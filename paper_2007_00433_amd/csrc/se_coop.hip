@@ -48,7 +48,7 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
     const uint32_t tile_end = min((blockIdx.x + 1u) * p.coop_tiles, p.tiles);
     for (uint32_t tile = blockIdx.x * p.coop_tiles; tile < tile_end; ++tile) {
         const uint32_t c = tile * 64u + (uint32_t)lane;
-        const bool valid = c < p.nvec;
+        const bool valid = c >= p.lead && c < p.nvec;
         const uint32_t off = c * (uint32_t)(VEC * 4);
         const uint32_t goff = BF16 ? off / 2 : off;
 

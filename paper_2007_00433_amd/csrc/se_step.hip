@@ -135,7 +135,7 @@ __global__ __launch_bounds__(64) void se_step_kernel(const StepArgs p)
     const uint64_t members = wave_members(p.seed, p.iter, p.n, p.m, g, lane);
 
     const uint32_t c = blockIdx.x * 64u + threadIdx.x;
-    if (c >= p.nvec) return;
+    if (c < p.lead || c >= p.nvec) return;
     const uint32_t off = c * (uint32_t)(VEC * 4);
     const uint32_t goff = BF16 ? off / 2 : off;
 

@@ -30,7 +30,8 @@ hipError_t record(const se::StepArgs &a, const se::LaunchShape &s, bool coop)
     EXPECT(a.pitch_bytes % fa == 0);
     if (a.v) EXPECT((uintptr_t)a.v % fa == 0);
     if (a.mode != se::kAvgOnly) { EXPECT(a.g != nullptr); EXPECT((uintptr_t)a.g % ga == 0); }
-    EXPECT(a.nvec > 0);
+    EXPECT(a.nvec > 0 && a.lead < 64u && a.lead < a.nvec);
+    if (a.lead) { EXPECT(s.vec == 4); EXPECT((uintptr_t)a.x % 1024u == 0); }   // only to reach a 1 KiB boundary
     EXPECT((uint64_t)a.nvec * (uint64_t)s.vec * 4u <= a.pitch_bytes);      // stays inside a row
     EXPECT(a.tiles == (a.nvec + 63u) / 64u);
     EXPECT(a.m >= 1 && a.m <= a.n && a.n <= se::kMaxWorkers && a.k * a.m == a.n);
@@ -41,7 +42,10 @@ hipError_t record(const se::StepArgs &a, const se::LaunchShape &s, bool coop)
         EXPECT((a.m + 3) / 4 <= 16);                                       // <= 1024 threads
         EXPECT(a.coop_tiles >= 1);
     }
-    g_recs.push_back({(uintptr_t)a.x, (uintptr_t)a.g, (uintptr_t)a.v, (uint64_t)a.nvec * (uint64_t)s.vec,
+    // what the launch touches: the columns behind the leading, switched-off lanes
+    const uint64_t skip = (uint64_t)a.lead * (uint64_t)s.vec;
+    g_recs.push_back({(uintptr_t)a.x + skip * 4u, a.g ? (uintptr_t)a.g + skip * (s.bf16 ? 2u : 4u) : 0,
+                      a.v ? (uintptr_t)a.v + skip * 4u : 0, (uint64_t)(a.nvec - a.lead) * (uint64_t)s.vec,
                       s.vec, coop, s.bf16, a.mode, a.m, a.k, a.tiles});
     return hipSuccess;
 }
