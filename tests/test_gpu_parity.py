@@ -219,6 +219,10 @@ def test_misaligned_base_addresses(shift, dtype):
     case = Case(8, 1536, dtype=dtype, shift=shift)
     run_ring(case, 2, 0.1, 0.9, 1e-2)
     case.check(f"ring shift {shift} {dtype}")
+    # long rows: a 128-bit range whose base is not 1 KiB aligned is split at the first boundary
+    case = Case(4, 70000, pitch=70000, dtype=dtype, shift=shift, distinct_rows=True, v_std=0.01)
+    run_sesgd(case, 2, 2, 0.1, 0.9, 1e-2)
+    case.check(f"long rows, shift {shift} {dtype}")
 
 
 @pytest.fixture
