@@ -115,13 +115,34 @@ def _ptr(buf) -> Optional[int]:
     raise TypeError(f"cannot take the address of {type(buf)}")
 
 
+def _rows(buf, n: int, pitch: int, elem_bytes: int, what: str) -> Optional[int]:
+    """Address of a device buffer of n rows of pitch elements.  The C ABI sees addresses only
+    and cannot know how much memory stands behind them, so a torch tensor is checked here for
+    device, contiguity, element size and length before its address is taken (a kernel that
+    runs past an allocation faults the GPU).  Integers and None pass through."""
+    if buf is not None and not isinstance(buf, int) and hasattr(buf, "data_ptr"):
+        if not buf.is_cuda:
+            raise ValueError(f"{what} must be a device tensor")
+        if not buf.is_contiguous():
+            raise ValueError(f"{what} must be contiguous")
+        if buf.element_size() != elem_bytes:
+            raise ValueError(f"{what} must have {elem_bytes}-byte elements, not {buf.dtype}")
+        if n > 0 and pitch > 0 and buf.numel() < n * pitch:
+            raise ValueError(f"{what} holds {buf.numel()} elements, fewer than n * pitch = {n * pitch}")
+    return _ptr(buf)
+
+
 def _offsets(layer_offsets: Sequence[int]) -> np.ndarray:
     return np.ascontiguousarray(np.asarray(layer_offsets, dtype=np.int64))
 
 
 def _stream(stream) -> Optional[int]:
+    """hipStream_t of a torch stream or an integer handle; None means torch's current stream
+    (not HIP's null stream, with which torch's side streams do not synchronise)."""
     if stream is None:
-        return None
+        if not torch.cuda.is_available():
+            return None
+        stream = torch.cuda.current_stream()
     if isinstance(stream, int):
         return stream or None
     return int(stream.cuda_stream) or None      # torch.cuda.Stream
@@ -168,7 +189,12 @@ def se_get_tuning(name: str) -> int:
 
 
 def se_calib_copy(dst, src, nbytes: int, stream=None) -> None:
-    check(lib.se_calib_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
+    for buf, what in ((dst, "dst"), (src, "src")):
+        if hasattr(buf, "data_ptr") and buf.numel() * buf.element_size() < nbytes:
+            raise ValueError(f"{what} is shorter than {nbytes} bytes")
+    check(lib.se_calib_copy(_rows(dst, 0, 0, dst.element_size() if hasattr(dst, "element_size") else 1, "dst"),
+                            _rows(src, 0, 0, src.element_size() if hasattr(src, "element_size") else 1, "src"),
+                            nbytes, _stream(stream)))
 
 
 def se_plan_raw(n, group_size, it, group_of_ptr, members_ptr) -> int:
@@ -187,8 +213,8 @@ def se_plan(n: int, group_size: int, it: int, want_members: bool = True):
 
 
 def se_plan_device(n: int, group_size: int, it: int, group_of_dev, members_dev=None, stream=None):
-    check(lib.se_plan_device(n, group_size, it, _ptr(group_of_dev), _ptr(members_dev),
-                             _stream(stream)))
+    check(lib.se_plan_device(n, group_size, it, _rows(group_of_dev, 1, n, 4, "group_of_dev"),
+                             _rows(members_dev, 1, n, 4, "members_dev"), _stream(stream)))
 
 
 def se_step_raw(fn_name, params, grads, momentum, layer_offsets, num_layers, n, group_size, it,
@@ -211,28 +237,38 @@ def se_ring_step_raw(fn_name, params, grads, momentum, layer_offsets, num_layers
 def se_step(params, grads, momentum, layer_offsets, n: int, group_size: int, it: int,
             lr: float, mu: float, stream=None) -> None:
     offs = _offsets(layer_offsets)
-    check(lib.se_step(_ptr(params), _ptr(grads), _ptr(momentum), offs.ctypes.data,
+    pitch = int(offs[-1])
+    check(lib.se_step(_rows(params, n, pitch, 4, "params"), _rows(grads, n, pitch, 4, "grads"),
+                      _rows(momentum, n, pitch, 4, "momentum"), offs.ctypes.data,
                       len(offs) - 1, n, group_size, it, lr, mu, _stream(stream)))
 
 
 def se_step_bf16g(params, grads_bf16, momentum, layer_offsets, n: int, group_size: int, it: int,
                   lr: float, mu: float, stream=None) -> None:
     offs = _offsets(layer_offsets)
-    check(lib.se_step_bf16g(_ptr(params), _ptr(grads_bf16), _ptr(momentum), offs.ctypes.data,
+    pitch = int(offs[-1])
+    check(lib.se_step_bf16g(_rows(params, n, pitch, 4, "params"),
+                            _rows(grads_bf16, n, pitch, 2, "grads_bf16"),
+                            _rows(momentum, n, pitch, 4, "momentum"), offs.ctypes.data,
                             len(offs) - 1, n, group_size, it, lr, mu, _stream(stream)))
 
 
 def se_ring_step(params, grads, momentum, layer_offsets, n: int, lr: float, mu: float,
                  stream=None) -> None:
     offs = _offsets(layer_offsets)
-    check(lib.se_ring_step(_ptr(params), _ptr(grads), _ptr(momentum), offs.ctypes.data,
+    pitch = int(offs[-1])
+    check(lib.se_ring_step(_rows(params, n, pitch, 4, "params"), _rows(grads, n, pitch, 4, "grads"),
+                           _rows(momentum, n, pitch, 4, "momentum"), offs.ctypes.data,
                            len(offs) - 1, n, lr, mu, _stream(stream)))
 
 
 def se_ring_step_bf16g(params, grads_bf16, momentum, layer_offsets, n: int, lr: float, mu: float,
                        stream=None) -> None:
     offs = _offsets(layer_offsets)
-    check(lib.se_ring_step_bf16g(_ptr(params), _ptr(grads_bf16), _ptr(momentum),
+    pitch = int(offs[-1])
+    check(lib.se_ring_step_bf16g(_rows(params, n, pitch, 4, "params"),
+                                 _rows(grads_bf16, n, pitch, 2, "grads_bf16"),
+                                 _rows(momentum, n, pitch, 4, "momentum"),
                                  offs.ctypes.data, len(offs) - 1, n, lr, mu, _stream(stream)))
 
 
@@ -250,22 +286,26 @@ def se_step_ex(params, grads, momentum, layer_offsets, n: int, group_size: int, 
                first_layer: int = 0, last_layer: Optional[int] = None,
                grads_are_bf16: bool = False, stream=None) -> None:
     offs = _offsets(layer_offsets)
+    pitch = int(offs[-1])
     last = len(offs) - 1 if last_layer is None else last_layer
-    check(lib.se_step_ex(_ptr(params), _ptr(grads), int(grads_are_bf16), _ptr(momentum),
+    check(lib.se_step_ex(_rows(params, n, pitch, 4, "params"),
+                         _rows(grads, n, pitch, 2 if grads_are_bf16 else 4, "grads"),
+                         int(grads_are_bf16), _rows(momentum, n, pitch, 4, "momentum"),
                          offs.ctypes.data, len(offs) - 1, first_layer, last, n, group_size, it,
                          lr, mu, weight_decay, flags, _stream(stream)))
 
 
 def se_global_average(params, layer_offsets, n: int, stream=None) -> None:
     offs = _offsets(layer_offsets)
-    check(lib.se_global_average(_ptr(params), offs.ctypes.data, len(offs) - 1, n, _stream(stream)))
+    check(lib.se_global_average(_rows(params, n, int(offs[-1]), 4, "params"), offs.ctypes.data,
+                                len(offs) - 1, n, _stream(stream)))
 
 
 def se_consensus(params, layer_offsets, n: int, out_dev, stream=None) -> None:
     """out_dev: device tensor of two float64 (distance to the mean, sum of parameters)."""
     offs = _offsets(layer_offsets)
-    check(lib.se_consensus(_ptr(params), offs.ctypes.data, len(offs) - 1, n, _ptr(out_dev),
-                           _stream(stream)))
+    check(lib.se_consensus(_rows(params, n, int(offs[-1]), 4, "params"), offs.ctypes.data,
+                           len(offs) - 1, n, _rows(out_dev, 1, 2, 8, "out_dev"), _stream(stream)))
 
 
 def se_comm_model(layer_offsets, elem_bytes: int, n: int, groups: int, bandwidth: float,

@@ -182,3 +182,36 @@ def test_comm_model_matches_the_oracle_and_the_paper():
     assert se.lib.se_comm_model(None, 1, 4, 16, 4, 1e9, 0.0, None, None, None, None) == se.SE_ERR_NULL
     assert se.lib.se_comm_model(offs_arr.ctypes.data, len(offs) - 1, 4, 16, 4, 1e9, 0.0,
                                 None, None, None, None) == se.SE_OK
+
+
+def test_binding_checks_tensors_before_taking_their_address():
+    """The checked wrappers refuse tensors the kernels would run past or misread (no GPU needed:
+    a host tensor is refused first of all)."""
+    import torch
+    offs = [0, 8]
+    host = torch.zeros(4, 8)
+    with pytest.raises(ValueError, match="device tensor"):
+        se.se_step(host, host, None, offs, 4, 2, 0, 0.1, 0.0)
+    with pytest.raises(ValueError, match="device tensor"):
+        se.se_global_average(host, offs, 4)
+
+    class Fake:            # stands in for a device tensor on a box without one
+        is_cuda = True
+        dtype = "fake"
+        def __init__(self, numel, elem=4, contiguous=True):
+            self._n, self._e, self._c = numel, elem, contiguous
+        def data_ptr(self): return 0x1000
+        def is_contiguous(self): return self._c
+        def element_size(self): return self._e
+        def numel(self): return self._n
+
+    with pytest.raises(ValueError, match="fewer than n \\* pitch"):
+        se.se_step(Fake(31), Fake(32), None, offs, 4, 2, 0, 0.1, 0.0)
+    with pytest.raises(ValueError, match="contiguous"):
+        se.se_ring_step(Fake(32), Fake(32, contiguous=False), None, offs, 4, 0.1, 0.0)
+    with pytest.raises(ValueError, match="2-byte elements"):
+        se.se_step_bf16g(Fake(32), Fake(32, elem=4), None, offs, 4, 2, 0, 0.1, 0.0)
+    with pytest.raises(ValueError, match="4-byte elements"):
+        se.se_step_ex(Fake(32), Fake(32, elem=2), None, offs, 4, 2, 0, 0.1, 0.0)
+    with pytest.raises(ValueError, match="8-byte elements"):
+        se.se_consensus(Fake(32), offs, 4, Fake(2, elem=4))
