@@ -8,15 +8,16 @@
 //   sum_i (x_i - xbar)^2 = sum_i d_i^2 - (sum_i d_i)^2 / n,   d_i = x_i - x_0,
 // where every d_i is exact in double precision (a difference of two floats), the right-hand
 // side cancels at most a factor n (x_0 is one of the samples), and identical rows give exactly
-// zero.  Workgroups of one wavefront stride over the tiles so that the tiles in flight are
-// neighbours; partial sums are reduced across the wavefront with lane shuffles and added to the
-// caller's two doubles with one fp64 atomic each per workgroup; a one-lane kernel clears them
-// first.
+// zero.  Wavefronts stride over the tiles so that the tiles in flight are neighbours; partial
+// sums are reduced across the wavefront with lane shuffles, across the four wavefronts of a
+// workgroup through LDS, and added to the caller's two doubles with one fp64 atomic each per
+// workgroup; a one-lane kernel clears them first.
 #include "se_device.hpp"
 
 namespace se {
 
-constexpr uint32_t kConsensusMaxGrid = 256u * 8u;     // 8 wavefronts per CU
+constexpr uint32_t kConsensusWaves = 4;               // wavefronts per workgroup
+constexpr uint32_t kConsensusMaxGrid = 256u * 2u;     // 8 wavefronts per CU
 constexpr int kConsensusBatch = 8;
 
 __global__ void se_clear2_kernel(double *out)
@@ -33,16 +34,22 @@ __device__ __forceinline__ double wave_sum(double v)
 }
 
 // x points at the first column of the range, nvec = columns / VEC, tiles = ceil(nvec / 64).
+// Every wavefront strides over the tiles on its own (wavefront w of workgroup b takes tiles
+// b + (4 i + w) * gridDim.x), so the tiles in flight are the same as with one-wavefront
+// workgroups; the workgroup only exists to add its wavefronts' sums with one pair of atomics
+// instead of four (an fp64 atomic on one address costs about 12 ns, and all workgroups arrive at
+// the end together).
 template <int VEC, bool NT>
-__global__ __launch_bounds__(64) void se_consensus_kernel(const float *__restrict__ x,
-                                                          uint64_t pitch_bytes, uint32_t nvec,
-                                                          uint32_t tiles, int n, double *out)
+__global__ __launch_bounds__(64 * kConsensusWaves) void se_consensus_kernel(
+    const float *__restrict__ x, uint64_t pitch_bytes, uint32_t nvec, uint32_t tiles, int n, double *out)
 {
-    const uint32_t lane = threadIdx.x;
+    __shared__ double part[2][kConsensusWaves];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     const double inv_n = 1.0 / (double)n;
     double dist = 0.0, total = 0.0;
-    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-        const uint32_t c = tile * 64u + lane;
+    for (uint64_t tile = blockIdx.x + (uint64_t)wave * gridDim.x; tile < tiles;
+         tile += (uint64_t)kConsensusWaves * gridDim.x) {
+        const uint32_t c = (uint32_t)tile * 64u + lane;
         if (c >= nvec) continue;
         const char *col = (const char *)x + (uint64_t)c * (uint64_t)(VEC * 4);
         const Pack<VEC> x0 = load_f32<VEC, NT>(col);
@@ -77,9 +84,12 @@ __global__ __launch_bounds__(64) void se_consensus_kernel(const float *__restric
     }
     dist = wave_sum(dist);
     total = wave_sum(total);
-    if (lane == 0) {
-        atomicAdd(out + 0, dist);
-        atomicAdd(out + 1, total);
+    if (lane == 0) { part[0][wave] = dist; part[1][wave] = total; }
+    __syncthreads();
+    static_assert(kConsensusWaves == 4, "the sums below add four partials");
+    if (threadIdx.x == 0) {
+        atomicAdd(out + 0, (part[0][0] + part[0][1]) + (part[0][2] + part[0][3]));
+        atomicAdd(out + 1, (part[1][0] + part[1][1]) + (part[1][2] + part[1][3]));
     }
 }
 
@@ -90,14 +100,15 @@ static hipError_t launch_part(const float *x, uint64_t pitch_elems, uint64_t nco
     if (ncols == 0) return hipSuccess;
     const uint32_t nvec = (uint32_t)(ncols / VEC);
     const uint32_t tiles = (nvec + 63u) / 64u;
-    const uint32_t grid = tiles < kConsensusMaxGrid ? tiles : kConsensusMaxGrid;
+    const uint32_t wgs = (tiles + kConsensusWaves - 1u) / kConsensusWaves;
+    const uint32_t grid = wgs < kConsensusMaxGrid ? wgs : kConsensusMaxGrid;
     // streaming loads once the rows cannot stay in the 256 MiB Infinity Cache anyway
     const bool nt = (uint64_t)n * ncols * 4u >= ((uint64_t)192 << 20);
     if (nt)
-        hipLaunchKernelGGL((se_consensus_kernel<VEC, true>), dim3(grid), dim3(64), 0, stream, x,
+        hipLaunchKernelGGL((se_consensus_kernel<VEC, true>), dim3(grid), dim3(64 * kConsensusWaves), 0, stream, x,
                            pitch_elems * 4u, nvec, tiles, n, out_dev);
     else
-        hipLaunchKernelGGL((se_consensus_kernel<VEC, false>), dim3(grid), dim3(64), 0, stream, x,
+        hipLaunchKernelGGL((se_consensus_kernel<VEC, false>), dim3(grid), dim3(64 * kConsensusWaves), 0, stream, x,
                            pitch_elems * 4u, nvec, tiles, n, out_dev);
     return hipGetLastError();
 }
