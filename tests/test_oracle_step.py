@@ -222,6 +222,29 @@ def test_full_group_is_ring_sgd_is_library_sgd_on_the_mean_gradient():
     assert np.max(np.abs(vs.astype(np.float64).mean(axis=0) - vr[0])) < 1e-7
 
 
+@pytest.mark.parametrize("n,dtype,lr,grad_std,T", [(64, "bf16", 1e-4, 1e-3, 10),
+                                                  (64, "f32", 0.1, 1e-3, 10),
+                                                  (32, "f32", 0.1, 1e-3, 20),
+                                                  (16, "f32", 0.1, 1e-2, 20)])
+def test_one_group_of_all_workers_is_ring_sgd_at_the_large_configurations(n, dtype, lr, grad_std, T):
+    """group_size = n against the DSGD equation (Sec. 3.2) at the settings of the largest
+    configuration: 64 workers, bf16 gradients ~ N(0, 1e-3), lr 1e-4, momentum 0.9, 10
+    iterations from identical starts.  The two differ only by the rounding of the sum of 64
+    values the size of x, which the two-level summation order keeps under the 1e-6 bar (a
+    plain left-to-right sum of 64 terms does not: it measures 2.4e-6 here)."""
+    P = 20000
+    xs = wl.host_params(n, P, 0.05, 12)
+    xr = xs.copy()
+    vs, vr = np.zeros_like(xs), np.zeros_like(xs)
+    for t in range(T):
+        g = wl.host_grads(n, P, grad_std, 12, t, dtype)
+        oracle.step(xs, g, vs, n, t, lr, 0.9)
+        oracle.ring_step(xr, g, vr, lr, 0.9)
+    assert layer_error(xs, xr, [0, P]) <= TOL
+    # every replica of the one group holds the same bits
+    assert bit_mismatches(xs, np.broadcast_to(xs[0], xs.shape).copy()) == 0
+
+
 def test_smaller_groups_follow_dsgd_in_the_mean():
     """For any group size the all-worker mean follows plain DSGD on the mean gradient
     (momentum is linear, so this holds with momentum too)."""
