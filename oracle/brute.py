@@ -3,7 +3,8 @@
 Independent of ``se_oracle.c``: exact rational arithmetic (``fractions.Fraction``) with
 an explicit round-to-nearest-even to binary32 after every fp32 operation, and no member
 lists -- every worker scans all workers and keeps those sharing its group, as the SESGD
-update equation (Sec. 3.2) is written.  Meant for n <= 8 and a handful of columns.
+update equation (Sec. 3.2) is written.  Meant for a handful of columns (n <= 8 for every group size; a few larger n to pin the
+summation order of groups of more than 8).
 """
 from __future__ import annotations
 
@@ -57,6 +58,25 @@ def mul32(a: Fraction, b: Fraction) -> Fraction:
     return rn32(a * b)
 
 
+BLOCK = 8
+
+
+def sum_in_order(vals) -> Fraction:
+    """The library's fixed summation order on a list of binary32 values (ascending worker id):
+    consecutive blocks of 8 are each added up left to right, then the block sums are added up
+    left to right, with one rounding per addition."""
+    parts = []
+    for b in range(0, len(vals), BLOCK):
+        part = vals[b]
+        for q in vals[b + 1:b + BLOCK]:
+            part = add32(part, q)
+        parts.append(part)
+    total = parts[0]
+    for part in parts[1:]:
+        total = add32(total, part)
+    return total
+
+
 def _mix32(z: int) -> int:
     z ^= z >> 16
     z = (z * 0x6A09E667) & _MASK
@@ -86,8 +106,9 @@ def brute_group_of(seed: int, n: int, m: int, it: int) -> list:
 def brute_step(x, g, v, group_of, m, lr, mu):
     """x, g: [n][P] nested lists/arrays of binary32-representable numbers; v the same or
     None.  Returns (x_new, v_new) as float32 arrays.  For every worker i on its own:
-    x_new[i] = (1/m) * sum over all j, ascending, with group_of[j] == group_of[i] of
-    xhat[j], where xhat[j] = x[j] - lr*v'[j] and v'[j] = mu*v[j] + g[j]."""
+    x_new[i] = (1/m) * sum (in the fixed order) over all j, ascending, with
+    group_of[j] == group_of[i] of xhat[j], where xhat[j] = x[j] - lr*v'[j] and
+    v'[j] = mu*v[j] + g[j]."""
     n = len(x)
     P = len(x[0])
     lr_q, mu_q = f32(lr), f32(mu)
@@ -102,10 +123,7 @@ def brute_step(x, g, v, group_of, m, lr, mu):
             vprime.append(vp)
             xhat.append(fma32(-lr_q, vp, f32(x[j][e])))
         for i in range(n):
-            s = None
-            for j in range(n):
-                if group_of[j] == group_of[i]:
-                    s = xhat[j] if s is None else add32(s, xhat[j])
+            s = sum_in_order([xhat[j] for j in range(n) if group_of[j] == group_of[i]])
             x_new[i, e] = np.float32(float(mul32(s, inv_m)))
             if v is not None:
                 v_new[i, e] = np.float32(float(vprime[i]))
@@ -121,10 +139,7 @@ def brute_ring_step(x, g, v, lr, mu):
     x_new = np.zeros((n, P), np.float32)
     v_new = None if v is None else np.zeros((n, P), np.float32)
     for e in range(P):
-        s = f32(g[0][e])
-        for j in range(1, n):
-            s = add32(s, f32(g[j][e]))
-        gbar = mul32(s, inv_n)
+        gbar = mul32(sum_in_order([f32(g[j][e]) for j in range(n)]), inv_n)
         for i in range(n):
             vp = gbar if v is None else fma32(mu_q, f32(v[i][e]), gbar)
             x_new[i, e] = np.float32(float(fma32(-lr_q, vp, f32(x[i][e]))))
@@ -146,10 +161,7 @@ def brute_step_ex(x, g, v, group_of, m, lr, mu, wd=0.0, grad_avg=False):
     for e in range(P):
         if grad_avg:
             for i in range(n):
-                s = None
-                for j in range(n):
-                    if group_of[j] == group_of[i]:
-                        s = f32(g[j][e]) if s is None else add32(s, f32(g[j][e]))
+                s = sum_in_order([f32(g[j][e]) for j in range(n) if group_of[j] == group_of[i]])
                 gbar = mul32(s, inv_m)
                 d = gbar if wd_q == 0 else fma32(wd_q, f32(x[i][e]), gbar)
                 vp = d if v is None else fma32(mu_q, f32(v[i][e]), d)
@@ -165,10 +177,7 @@ def brute_step_ex(x, g, v, group_of, m, lr, mu, wd=0.0, grad_avg=False):
                 vprime.append(vp)
                 xhat.append(fma32(-lr_q, vp, f32(x[j][e])))
             for i in range(n):
-                s = None
-                for j in range(n):
-                    if group_of[j] == group_of[i]:
-                        s = xhat[j] if s is None else add32(s, xhat[j])
+                s = sum_in_order([xhat[j] for j in range(n) if group_of[j] == group_of[i]])
                 x_new[i, e] = np.float32(float(mul32(s, inv_m)))
                 if v is not None:
                     v_new[i, e] = np.float32(float(vprime[i]))
@@ -181,8 +190,6 @@ def brute_global_average(x):
     inv_n = rn32(Fraction(1) / f32(n))
     out = np.zeros((n, P), np.float32)
     for e in range(P):
-        s = f32(x[0][e])
-        for j in range(1, n):
-            s = add32(s, f32(x[j][e]))
+        s = sum_in_order([f32(x[j][e]) for j in range(n)])
         out[:, e] = np.float32(float(mul32(s, inv_n)))
     return out

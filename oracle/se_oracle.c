@@ -25,7 +25,12 @@
  *     one buffer per worker, never averaged (Algorithm 1 all-reduces x-hat only).
  *   - Baseline (Sec. 3.2, the DSGD equation): mean gradient over all n workers, the same
  *     update on every worker.
- *   - Summation order: members in ascending worker id, left to right (paper is silent).
+ *   - Summation order (paper is silent; a convention of this build, the same wherever rows
+ *     are reduced): the members in ascending worker id are cut into consecutive blocks of 8
+ *     (the last one may be shorter), each block is summed left to right, then the block sums
+ *     are added left to right.  Up to 8 members that is the plain left-to-right sum.  A
+ *     left-to-right sum of 64 values of the size of x would put group_size = n = 64 further
+ *     than 1e-6 from the DSGD equation it must reduce to (Sec. 3.2).
  */
 #include <math.h>
 #include <stddef.h>
@@ -109,6 +114,22 @@ int oracle_plan(uint64_t seed, int n, int m, int64_t iter,
     return ORACLE_OK;
 }
 
+/* The fixed summation order: blocks of ORACLE_BLOCK consecutive values left to right, then
+ * the block sums left to right.  val[0..m-1] are in ascending worker id. */
+#define ORACLE_BLOCK 8
+static float sum_in_order(const float *val, int m)
+{
+    float total = 0.0f;
+    int b, r;
+    for (b = 0; b < m; b += ORACLE_BLOCK) {
+        float part = val[b];
+        for (r = b + 1; r < m && r < b + ORACLE_BLOCK; ++r)
+            part = part + val[r];
+        total = (b == 0) ? part : total + part;
+    }
+    return total;
+}
+
 /* bf16 -> fp32 is exact: the 16 bits are the high half of the fp32 pattern. */
 static float bf16_to_f32(uint16_t b)
 {
@@ -131,9 +152,9 @@ static float load_grad(const void *grads, int grads_are_bf16, int64_t idx)
  *
  *   for every group G of this iteration's plan, every column e:
  *     for members j of G in ascending id:
- *        v'   = momentum ? fmaf(mu, momentum[j][e], g[j][e]) : g[j][e]
- *        xhat = fmaf(-lr, v', params[j][e])
- *        s    = (first member) ? xhat : s + xhat
+ *        v'      = momentum ? fmaf(mu, momentum[j][e], g[j][e]) : g[j][e]
+ *        xhat[j] = fmaf(-lr, v', params[j][e])
+ *     s    = the xhat[j] summed in the fixed order (blocks of 8, then the block sums)
  *     mean = s * (1.0f / (float)m)
  *     params[j][e] = mean for every member j;  momentum[j][e] = v'
  *
@@ -145,6 +166,7 @@ int oracle_step(float *params, const void *grads, int grads_are_bf16, float *mom
 {
     int32_t group_of[ORACLE_MAX_N];
     int32_t members[ORACLE_MAX_N];
+    float xhat[ORACLE_MAX_N];
     int rc, g, r, k;
     int64_t e;
     float inv_m;
@@ -159,21 +181,20 @@ int oracle_step(float *params, const void *grads, int grads_are_bf16, float *mom
     for (g = 0; g < k; ++g) {
         const int32_t *mem = members + (size_t)g * m;
         for (e = col_begin; e < col_end; ++e) {
-            float s = 0.0f, mean;
+            float mean;
             for (r = 0; r < m; ++r) {
                 int64_t idx = (int64_t)mem[r] * pitch + e;
                 float gg = load_grad(grads, grads_are_bf16, idx);
-                float vn, xhat;
+                float vn;
                 if (momentum) {
                     vn = fmaf(mu, momentum[idx], gg);
                     momentum[idx] = vn;
                 } else {
                     vn = gg;
                 }
-                xhat = fmaf(-lr, vn, params[idx]);
-                s = (r == 0) ? xhat : s + xhat;
+                xhat[r] = fmaf(-lr, vn, params[idx]);
             }
-            mean = s * inv_m;
+            mean = sum_in_order(xhat, m) * inv_m;
             for (r = 0; r < m; ++r)
                 params[(int64_t)mem[r] * pitch + e] = mean;
         }
@@ -183,7 +204,7 @@ int oracle_step(float *params, const void *grads, int grads_are_bf16, float *mom
 
 /*
  * One Ring-SGD (fully synchronous DSGD) iteration (Sec. 3.2, the DSGD equation):
- *   gbar = (g[0][e] + g[1][e] + ... + g[n-1][e]) * (1.0f / (float)n)   (left to right)
+ *   gbar = (g[0][e], g[1][e], ..., g[n-1][e] summed in the fixed order) * (1.0f / (float)n)
  *   v'   = momentum ? fmaf(mu, momentum[i][e], gbar) : gbar
  *   params[i][e] = fmaf(-lr, v', params[i][e])          for every worker i
  */
@@ -191,19 +212,19 @@ int oracle_ring_step(float *params, const void *grads, int grads_are_bf16, float
                      int64_t pitch, int64_t col_begin, int64_t col_end,
                      int n, float lr, float mu)
 {
+    float gcol[ORACLE_MAX_N];
     int i;
     int64_t e;
     float inv_n;
-    if (params == NULL || grads == NULL || n < 1 || pitch < 0 || col_begin < 0 ||
+    if (params == NULL || grads == NULL || n < 1 || n > ORACLE_MAX_N || pitch < 0 || col_begin < 0 ||
         col_end < col_begin || col_end > pitch)
         return ORACLE_ERR_ARG;
     inv_n = 1.0f / (float)n;
     for (e = col_begin; e < col_end; ++e) {
-        float s = load_grad(grads, grads_are_bf16, e);
         float gbar;
-        for (i = 1; i < n; ++i)
-            s = s + load_grad(grads, grads_are_bf16, (int64_t)i * pitch + e);
-        gbar = s * inv_n;
+        for (i = 0; i < n; ++i)
+            gcol[i] = load_grad(grads, grads_are_bf16, (int64_t)i * pitch + e);
+        gbar = sum_in_order(gcol, n) * inv_n;
         for (i = 0; i < n; ++i) {
             int64_t idx = (int64_t)i * pitch + e;
             float vn;
@@ -237,7 +258,7 @@ int oracle_ring_step(float *params, const void *grads, int grads_are_bf16, float
  *   oracle_step when wd == 0.
  * flags & ORACLE_FLAG_GRAD_AVG: the variant the paper rejects (Sec. 3.2: the shuffle applied
  *   directly to the DSGD equation).  The *gradients* are averaged inside the group,
- *     gbar_G = (g_{j0} + g_{j1} + ...) * (1.0f/(float)m)      members ascending, left to right
+ *     gbar_G = (g_{j0}, g_{j1}, ... summed in the fixed order) * (1.0f/(float)m)   members ascending
  *   and every member updates on its own: gsrc = gbar_G,
  *     v_j = momentum ? fmaf(mu, v_j, d_j) : d_j ;  x_j = fmaf(-lr, v_j, x_j).
  *   Parameters are never averaged, so replicas drift apart (the paper's divergence equation).
@@ -250,6 +271,7 @@ int oracle_step_ex(float *params, const void *grads, int grads_are_bf16, float *
 {
     int32_t group_of[ORACLE_MAX_N];
     int32_t members[ORACLE_MAX_N];
+    float val[ORACLE_MAX_N];
     int rc, g, r, k;
     int64_t e;
     float inv_m;
@@ -265,12 +287,10 @@ int oracle_step_ex(float *params, const void *grads, int grads_are_bf16, float *
         const int32_t *mem = members + (size_t)g * m;
         for (e = col_begin; e < col_end; ++e) {
             if (flags & ORACLE_FLAG_GRAD_AVG) {
-                float s = 0.0f, gbar;
-                for (r = 0; r < m; ++r) {
-                    float gg = load_grad(grads, grads_are_bf16, (int64_t)mem[r] * pitch + e);
-                    s = (r == 0) ? gg : s + gg;
-                }
-                gbar = s * inv_m;
+                float gbar;
+                for (r = 0; r < m; ++r)
+                    val[r] = load_grad(grads, grads_are_bf16, (int64_t)mem[r] * pitch + e);
+                gbar = sum_in_order(val, m) * inv_m;
                 for (r = 0; r < m; ++r) {
                     int64_t idx = (int64_t)mem[r] * pitch + e;
                     float d = (wd != 0.0f) ? fmaf(wd, params[idx], gbar) : gbar;
@@ -284,22 +304,21 @@ int oracle_step_ex(float *params, const void *grads, int grads_are_bf16, float *
                     params[idx] = fmaf(-lr, vn, params[idx]);
                 }
             } else {
-                float s = 0.0f, mean;
+                float mean;
                 for (r = 0; r < m; ++r) {
                     int64_t idx = (int64_t)mem[r] * pitch + e;
                     float gg = load_grad(grads, grads_are_bf16, idx);
                     float d = (wd != 0.0f) ? fmaf(wd, params[idx], gg) : gg;
-                    float vn, xhat;
+                    float vn;
                     if (momentum) {
                         vn = fmaf(mu, momentum[idx], d);
                         momentum[idx] = vn;
                     } else {
                         vn = d;
                     }
-                    xhat = fmaf(-lr, vn, params[idx]);
-                    s = (r == 0) ? xhat : s + xhat;
+                    val[r] = fmaf(-lr, vn, params[idx]);
                 }
-                mean = s * inv_m;
+                mean = sum_in_order(val, m) * inv_m;
                 for (r = 0; r < m; ++r)
                     params[(int64_t)mem[r] * pitch + e] = mean;
             }
@@ -310,21 +329,24 @@ int oracle_step_ex(float *params, const void *grads, int grads_are_bf16, float *
 
 /*
  * Final global average (Algorithm 1, last line: x-bar <- Ring-AllReduce(x_i; Global)):
- *   xbar[e] = (x_0[e] + x_1[e] + ... + x_{n-1}[e]) * (1.0f/(float)n), written to every row.
+ *   xbar[e] = (x_0[e], x_1[e], ..., x_{n-1}[e] summed in the fixed order) * (1.0f/(float)n),
+ *   written to every row.
  */
 int oracle_global_average(float *params, int64_t pitch, int64_t col_begin, int64_t col_end, int n)
 {
+    float xcol[ORACLE_MAX_N];
     int i;
     int64_t e;
     float inv_n;
-    if (params == NULL || n < 1 || pitch < 0 || col_begin < 0 || col_end < col_begin || col_end > pitch)
+    if (params == NULL || n < 1 || n > ORACLE_MAX_N || pitch < 0 || col_begin < 0 ||
+        col_end < col_begin || col_end > pitch)
         return ORACLE_ERR_ARG;
     inv_n = 1.0f / (float)n;
     for (e = col_begin; e < col_end; ++e) {
-        float s = params[e], mean;
-        for (i = 1; i < n; ++i)
-            s = s + params[(int64_t)i * pitch + e];
-        mean = s * inv_n;
+        float mean;
+        for (i = 0; i < n; ++i)
+            xcol[i] = params[(int64_t)i * pitch + e];
+        mean = sum_in_order(xcol, n) * inv_n;
         for (i = 0; i < n; ++i)
             params[(int64_t)i * pitch + e] = mean;
     }

@@ -13,22 +13,32 @@ import test_oracle_step as step_pins
 SRC = os.path.join(os.path.dirname(oracle.__file__), "se_oracle.c")
 
 MUTANTS = {
-    "sign of the learning-rate term": ("xhat = fmaf(-lr, vn, params[idx]);", "xhat = fmaf(lr, vn, params[idx]);"),
+    "sign of the learning-rate term": ("xhat[r] = fmaf(-lr, vn, params[idx]);", "xhat[r] = fmaf(lr, vn, params[idx]);"),
     "momentum operands transposed": ("vn = fmaf(mu, momentum[idx], gg);", "vn = fmaf(mu, gg, momentum[idx]);"),
     "momentum term dropped": ("vn = fmaf(mu, momentum[idx], gg);", "vn = gg;"),
     "momentum not written back": ("                    momentum[idx] = vn;\n                } else {\n                    vn = gg;",
                                   "                } else {\n                    vn = gg;"),
-    "learning rate applied to g instead of v'": ("xhat = fmaf(-lr, vn, params[idx]);", "xhat = fmaf(-lr, gg, params[idx]);"),
-    "mean not scaled": ("mean = s * inv_m;", "mean = s;"),
+    "learning rate applied to g instead of v'": ("xhat[r] = fmaf(-lr, vn, params[idx]);", "xhat[r] = fmaf(-lr, gg, params[idx]);"),
+    "mean not scaled": ("mean = sum_in_order(xhat, m) * inv_m;", "mean = sum_in_order(xhat, m);"),
     "scaled by groups instead of group size": ("inv_m = 1.0f / (float)m;", "inv_m = 1.0f / (float)k;"),
     "mean written to the first member only": ("params[(int64_t)mem[r] * pitch + e] = mean;", "params[(int64_t)mem[0] * pitch + e] = mean;"),
-    "first member counted twice": ("s = (r == 0) ? xhat : s + xhat;", "s = (r == 0) ? xhat + xhat : s + xhat;"),
-    "unfused multiply-add": ("xhat = fmaf(-lr, vn, params[idx]);", "xhat = params[idx] + (-lr * vn);"),
+    "first member counted twice": ("float part = val[b];", "float part = val[b] + (b == 0 ? val[0] : 0.0f);"),
+    # --- the summation order
+    "plain left-to-right sum": ("#define ORACLE_BLOCK 8", "#define ORACLE_BLOCK 4096"),
+    "blocks of 7": ("#define ORACLE_BLOCK 8", "#define ORACLE_BLOCK 7"),
+    "blocks of 9": ("#define ORACLE_BLOCK 8", "#define ORACLE_BLOCK 9"),
+    "blocks of 4": ("#define ORACLE_BLOCK 8", "#define ORACLE_BLOCK 4"),
+    "block sums added last to first": ("for (b = 0; b < m; b += ORACLE_BLOCK) {\n        float part = val[b];",
+                                       "for (b = (m - 1) / ORACLE_BLOCK * ORACLE_BLOCK; b >= 0; b -= ORACLE_BLOCK) {\n        float part = val[b];"),
+    "first block sum restarted by the second": ("total = (b == 0) ? part : total + part;", "total = (b <= ORACLE_BLOCK) ? part : total + part;"),
+    "last member of a block dropped": ("for (r = b + 1; r < m && r < b + ORACLE_BLOCK; ++r)", "for (r = b + 1; r < m && r < b + ORACLE_BLOCK - 1; ++r)"),
+    "unfused multiply-add": ("xhat[r] = fmaf(-lr, vn, params[idx]);", "xhat[r] = params[idx] + (-lr * vn);"),
     "groups cut by remainder": ("group_of[i] = below / m;", "group_of[i] = below % (n / m);"),
     "hash shift": ("z ^= z >> 15;", "z ^= z >> 13;"),
     "hash skips the iteration word": ("w[2] = (uint32_t)(t & 0xFFFFFFFFu);", "w[2] = 0;"),
-    "ring mean not scaled": ("gbar = s * inv_n;", "gbar = s;"),
-    "ring counts worker 0 twice": ("for (i = 1; i < n; ++i)\n            s = s +", "for (i = 0; i < n; ++i)\n            s = s +"),
+    "ring mean not scaled": ("gbar = sum_in_order(gcol, n) * inv_n;", "gbar = sum_in_order(gcol, n);"),
+    "ring reads worker 0 in place of the last worker": ("gcol[i] = load_grad(grads, grads_are_bf16, (int64_t)i * pitch + e);",
+                                                         "gcol[i] = load_grad(grads, grads_are_bf16, (int64_t)(i == n - 1 ? 0 : i) * pitch + e);"),
     "ring update sign": ("params[idx] = fmaf(-lr, vn, params[idx]);", "params[idx] = fmaf(lr, vn, params[idx]);"),
     # --- the extended functions
     "decay sign (corrected form)": ("float d = (wd != 0.0f) ? fmaf(wd, params[idx], gg) : gg;",
@@ -37,11 +47,10 @@ MUTANTS = {
                                                          "float d = (wd != 0.0f) ? fmaf(wd, gg, gg) : gg;"),
     "decay dropped in the gradient-averaging form": ("float d = (wd != 0.0f) ? fmaf(wd, params[idx], gbar) : gbar;",
                                                      "float d = gbar;"),
-    "gradient mean not scaled": ("gbar = s * inv_m;\n                for (r = 0; r < m; ++r) {", "gbar = s;\n                for (r = 0; r < m; ++r) {"),
+    "gradient mean not scaled": ("gbar = sum_in_order(val, m) * inv_m;", "gbar = sum_in_order(val, m);"),
     "gradient-averaging form averages parameters too": ("                    params[idx] = fmaf(-lr, vn, params[idx]);\n                }\n            } else {",
                                                         "                    params[idx] = fmaf(-lr, vn, params[(int64_t)mem[0] * pitch + e]);\n                }\n            } else {"),
-    "global average skips the last worker": ("for (i = 1; i < n; ++i)\n            s = s + params[(int64_t)i * pitch + e];",
-                                             "for (i = 1; i < n - 1; ++i)\n            s = s + params[(int64_t)i * pitch + e];"),
+    "global average skips the last worker": ("mean = sum_in_order(xcol, n) * inv_n;", "mean = sum_in_order(xcol, n - (n > 1)) * inv_n;"),
     "consensus uses the sum as the mean": ("mean = s / (double)n;", "mean = s;"),
     "consensus forgets the square": ("d += t * t;", "d += t;"),
     "ring time drops the latency term": ("(layer_bytes / ((double)workers * nu) + t_tau)", "(layer_bytes / ((double)workers * nu))"),
@@ -56,6 +65,9 @@ def battery(golden_dir):
         ("sign/operand", step_pins.test_sign_and_operand_order_are_observable),
         ("brute n=2", lambda: step_pins.test_brute_force_exact_rational(2)),
         ("brute n=4", lambda: step_pins.test_brute_force_exact_rational(4)),
+        ("summation order by hand", lambda: step_pins.test_summation_order_examples_by_hand(golden_dir)),
+        ("brute n=20, m=10", lambda: step_pins.test_brute_force_exact_rational_for_groups_of_more_than_eight(20, 10)),
+        ("ring brute n=17", lambda: step_pins.test_ring_brute_force_exact_rational_for_more_than_eight_workers(17)),
         ("ring brute n=5", lambda: step_pins.test_ring_brute_force_exact_rational(5)),
         ("conservation", step_pins.test_conservation_of_the_all_worker_sum),
         ("consensus", step_pins.test_members_of_a_group_end_bit_identical),

@@ -122,6 +122,75 @@ def test_ring_brute_force_exact_rational(n):
                 assert same_values(v, want_v)
 
 
+@pytest.mark.parametrize("n,m", [(9, 9), (12, 12), (16, 16), (18, 9), (20, 10), (24, 24), (32, 16),
+                                 (40, 20), (64, 64), (63, 21)])
+def test_brute_force_exact_rational_for_groups_of_more_than_eight(n, m):
+    """The two-level summation order (blocks of 8 members, then the block sums) against the
+    exact-rational brute force, including ragged last blocks (9 = 8+1, 12 = 8+4, 20 = 8+8+4)."""
+    rng = np.random.default_rng(300 + n)
+    P = 3
+    for use_v in (True, False):
+        x = _random_f32(rng, (n, P), 1.0)
+        v = _random_f32(rng, (n, P), 0.1) if use_v else None
+        for it in (0, 5):
+            g = _random_f32(rng, (n, P), 1e-2)
+            group_of = oracle.plan(n, m, it)["group_of"].tolist()
+            want_x, want_v = brute.brute_step(x, g, v, group_of, m, np.float32(0.1), np.float32(0.9))
+            oracle.step(x, g, v, m, it, 0.1, 0.9)
+            assert same_values(x, want_x)
+            if use_v:
+                assert same_values(v, want_v)
+
+
+@pytest.mark.parametrize("n", [9, 16, 17, 33, 64])
+def test_ring_brute_force_exact_rational_for_more_than_eight_workers(n):
+    rng = np.random.default_rng(400 + n)
+    P = 3
+    x = _random_f32(rng, (n, P), 1.0)
+    v = _random_f32(rng, (n, P), 0.1)
+    for _ in range(2):
+        g = _random_f32(rng, (n, P), 1e-2)
+        want_x, want_v = brute.brute_ring_step(x, g, v, np.float32(0.1), np.float32(0.9))
+        oracle.ring_step(x, g, v, 0.1, 0.9)
+        assert same_values(x, want_x) and same_values(v, want_v)
+
+
+def test_summation_order_examples_by_hand(golden_dir):
+    """Hand-evaluated sums that tell the documented order (blocks of 8 in ascending worker id,
+    then the block sums first to last) from its neighbours: left to right, other block sizes,
+    reversed orders.  One column, one group of all workers; lr = 0 keeps x-hat = x."""
+    with open(os.path.join(golden_dir, "summation_order_examples.json")) as f:
+        cases = json.load(f)["cases"]
+    for c in cases:
+        vals = np.asarray(c["values"], np.float32)
+        n = vals.size
+        assert n & (n - 1) == 0                                  # the mean is then exact
+        mean = np.float32(c["sum"]) / np.float32(n)
+        assert float(mean) * n == c["sum"]
+        for wrong in c["other_orders"].values():
+            assert wrong != c["sum"]
+        # SESGD update with one group and lr = 0: the group mean of x itself
+        x = vals.reshape(n, 1).copy()
+        oracle.step(x, np.ones_like(x), None, n, 0, 0.0, 0.0)
+        assert (x == mean).all(), c["name"]
+        # the same through the general step, the global average and the brute force
+        x = vals.reshape(n, 1).copy()
+        oracle.step_ex(x, np.ones_like(x), None, n, 0, 0.0, 0.0, 0.0, 0)
+        assert (x == mean).all(), c["name"]
+        x = vals.reshape(n, 1).copy()
+        oracle.global_average(x)
+        assert (x == mean).all(), c["name"]
+        bx, _ = brute.brute_step(vals.reshape(n, 1), np.ones((n, 1), np.float32), None, [0] * n, n,
+                                 np.float32(0.0), np.float32(0.0))
+        assert (bx == mean).all(), c["name"]
+        # Ring-SGD / gradient averaging: the values are the gradients, x = 0, lr = -1
+        for fn in (lambda x, g: oracle.ring_step(x, g, None, -1.0, 0.0),
+                   lambda x, g: oracle.step_ex(x, g, None, n, 0, -1.0, 0.0, 0.0, oracle.FLAG_GRAD_AVG)):
+            x = np.zeros((n, 1), np.float32)
+            fn(x, vals.reshape(n, 1).copy())
+            assert (x == mean).all(), c["name"]
+
+
 def test_rn32_rounding_helper_against_numpy():
     """The brute force's own rounding is checked against numpy's float64->float32 cast on
     values that a double holds exactly (so the cast rounds once)."""
