@@ -1,30 +1,34 @@
 // Cooperative form of the step kernels for many rows per reduction (large groups, and the
-// Ring-SGD baseline where all n rows are reduced): the rows of one group are split over the
-// wavefronts of a workgroup, kRowsPerWave rows each, all wavefronts covering the same 64
-// lane-columns.  Every lane issues all loads of its rows at once (one round trip to HBM),
-// stages the values to be reduced in LDS, and after one barrier every wavefront walks the
-// staged rows in ascending worker id -- the documented summation order, so the result is
-// bit-identical to the single-wavefront form -- and finishes its own rows.
+// Ring-SGD baseline where all n rows are reduced).  The library adds a group's values up in
+// blocks of 8 members (ascending worker id, left to right) and then adds the block sums left to
+// right; here every wavefront of a workgroup owns one such block: it issues all loads of its 8
+// rows at once (one round trip to HBM), adds its block up in registers, stages the ONE block sum
+// in LDS (1 KiB per wavefront), and after one barrier every wavefront adds the staged block sums
+// in order -- the same tree, hence the same bits, as the single-wavefront form -- and finishes
+// its own 8 rows.  A wavefront thus reads and writes 8 rows only, and a workgroup of ceil(m/8)
+// wavefronts covers the same 64 lane-columns of all m rows.
 //
-//   kSesgd   (Sec. 3.2, the SESGD update equation): stage x-hat; mean -> own rows.
+//   kSesgd   (Sec. 3.2, the SESGD update equation): block sums of x-hat; mean -> own rows.
 //   kGradAvg (Sec. 3.2, the DSGD equation applied per group; Ring-SGD when the group is all n
-//            workers): stage g; mean gradient -> momentum/SGD update of own rows, whose x and v
-//            were loaded together with g.
-//   kAvgOnly (Algorithm 1, last line): stage x; mean -> own rows.
+//            workers): block sums of g; mean gradient -> momentum/SGD update of own rows, whose
+//            x and v were loaded together with g.
+//   kAvgOnly (Algorithm 1, last line): block sums of x; mean -> own rows.
 #include "se_device.hpp"
 
 #include <atomic>
 
 namespace se {
 
-constexpr int kRowsPerWave = 4;
+constexpr int kRowsPerWave = 8;      // = the block length of the summation order
 
 template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, int NT, int MODE>
-__global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
+__global__ __launch_bounds__(64 * ((kMaxWorkers + kRowsPerWave - 1) / kRowsPerWave))
+void se_coop_kernel(const StepArgs p)
 {
-    extern __shared__ float staged[];          // [rows][64 lanes][VEC]
+    extern __shared__ float staged[];          // [wavefronts][64 lanes][VEC]: one block sum each
     const int lane = (int)(threadIdx.x & 63u);
     const int wave = (int)(threadIdx.x >> 6);
+    const int blocks = (p.m + kRowsPerWave - 1) / kRowsPerWave;     // = wavefronts of the workgroup
     const uint64_t gpitch_bytes = BF16 ? p.pitch_bytes / 2 : p.pitch_bytes;
 
     const uint32_t g = blockIdx.y;
@@ -42,9 +46,7 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
         todo &= todo - 1;
     }
 
-    // A workgroup walks through coop_tiles consecutive tiles.  One tile per workgroup keeps
-    // neighbouring tiles in flight together, which DRAM likes best; only with very many rows
-    // (192 row streams at m = 64) a few tiles per workgroup measure faster.
+    // A workgroup walks through coop_tiles consecutive tiles.
     const uint32_t tile_end = min((blockIdx.x + 1u) * p.coop_tiles, p.tiles);
     for (uint32_t tile = blockIdx.x * p.coop_tiles; tile < tile_end; ++tile) {
         const uint32_t c = tile * 64u + (uint32_t)lane;
@@ -65,6 +67,7 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
                     }
                 }
             }
+            Pack<VEC> part;                    // this block's sum, members left to right
 #pragma unroll
             for (int r = 0; r < kRowsPerWave; ++r) {
                 if (r < mine) {
@@ -84,15 +87,17 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
                         if constexpr (HAS_V)
                             store_f32<VEC, NT>((char *)p.v + row[r] * p.pitch_bytes, off, vn);
                     }
-                    store_f32<VEC, kPlain>((char *)(staged + ((size_t)(first + r) * 64 + lane) * VEC), 0u, out);
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) part.a[q] = r == 0 ? out.a[q] : part.a[q] + out.a[q];
                 }
             }
+            store_f32<VEC, kPlain>((char *)(staged + ((size_t)wave * 64 + lane) * VEC), 0u, part);
         }
         __syncthreads();
         if (valid) {
             Pack<VEC> s = load_f32<VEC, kPlain>((const char *)(staged + (size_t)lane * VEC));
-            for (int r = 1; r < p.m; ++r) {
-                const Pack<VEC> t = load_f32<VEC, kPlain>((const char *)(staged + ((size_t)r * 64 + lane) * VEC));
+            for (int b = 1; b < blocks; ++b) {
+                const Pack<VEC> t = load_f32<VEC, kPlain>((const char *)(staged + ((size_t)b * 64 + lane) * VEC));
 #pragma unroll
                 for (int q = 0; q < VEC; ++q) s.a[q] = s.a[q] + t.a[q];
             }
@@ -129,8 +134,8 @@ __global__ __launch_bounds__(1024) void se_coop_kernel(const StepArgs p)
 template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, int NT, int MODE>
 static hipError_t launch_one(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
-    const int waves = (a.m + kRowsPerWave - 1) / kRowsPerWave;     // <= 16 for m <= 64
-    const size_t need = (size_t)a.m * 64 * VEC * sizeof(float);    // <= 64 KiB
+    const int waves = (a.m + kRowsPerWave - 1) / kRowsPerWave;     // <= 8 for m <= 64
+    const size_t need = (size_t)waves * 64 * VEC * sizeof(float);  // <= 8 KiB
     const size_t lds = need > s.lds_bytes ? need : s.lds_bytes;
     auto kern = se_coop_kernel<VEC, BF16, HAS_V, HAS_WD, NT, MODE>;
     static std::atomic<uint64_t> allowed{0};

@@ -4,8 +4,9 @@
 // A wavefront touches 64*VEC*4 contiguous bytes of each member row per access.
 //
 // The member list of group g is the bit mask ballot(group_of(lane) == g): iterating its set
-// bits visits the members in ascending worker id, which is the summation order the library
-// documents.  All of that is wave-uniform, so row bases live in scalar registers.
+// bits visits the members in ascending worker id; they are added up in the order the library
+// documents (blocks of 8 members left to right, then the block sums left to right).  All of
+// that is wave-uniform, so row bases live in scalar registers.
 //
 // Modes
 //   kSesgd   Sec. 3.2 "Gradient Correction", the SESGD update equation; Algorithm 1 loop body:
@@ -104,8 +105,8 @@ __device__ __forceinline__ void update_batch(const StepArgs &p, uint64_t &todo, 
     }
 }
 
-// Applies CALL(B, FIRST) to all m members in batches of BMAX, then 4, 2, 1; FIRST is true for
-// the batch that holds the group's first member (wave-uniform control flow throughout).
+// Applies CALL(B, FIRST) to all m members in batches of BMAX, then 4, 2, 1 (wave-uniform control
+// flow throughout); FIRST is true for the first batch.  For passes that do not add anything up.
 #define SE_FOR_MEMBER_BATCHES(BMAX, m, CALL)                                               \
     do {                                                                                   \
         int rem_ = (m);                                                                    \
@@ -120,6 +121,40 @@ __device__ __forceinline__ void update_batch(const StepArgs &p, uint64_t &todo, 
             if (first_) { CALL(2, true); } else { CALL(2, false); } rem_ -= 2; first_ = false; } } \
         if constexpr (BMAX > 1) { if (rem_ >= 1) {                                         \
             if (first_) { CALL(1, true); } else { CALL(1, false); } } }                    \
+    } while (0)
+
+// The library's summation order: the m members (ascending worker id) are cut into consecutive
+// blocks of kSumBlock = 8, each block is added up left to right, then the block sums are added
+// up left to right.  CALL(B, FIRST, acc) must add B members to acc, left to right, starting acc
+// afresh when FIRST.  A full block is one batch of 8 (BMAX == 8) or two of 4; a shorter last
+// block is walked in batches of 4, 2, 1.  The total lands in `total`.
+constexpr int kSumBlock = 8;
+#define SE_SUM_MEMBER_BLOCKS(BMAX, m, VEC_, total, CALL)                                   \
+    do {                                                                                   \
+        static_assert(BMAX == 8 || BMAX == 4, "batch size");                               \
+        int rem_ = (m);                                                                    \
+        bool first_block_ = true;                                                          \
+        while (rem_ > 0) {                                                                 \
+            Pack<VEC_> part_;                                                              \
+            if (rem_ >= kSumBlock) {                                                       \
+                if constexpr (BMAX == 8) { CALL(8, true, part_); }                         \
+                else { CALL(4, true, part_); CALL(4, false, part_); }                      \
+                rem_ -= kSumBlock;                                                         \
+            } else {                                                                       \
+                bool first_ = true;                                                        \
+                if (rem_ >= 4) { CALL(4, true, part_); rem_ -= 4; first_ = false; }        \
+                if (rem_ >= 2) {                                                           \
+                    if (first_) { CALL(2, true, part_); } else { CALL(2, false, part_); }  \
+                    rem_ -= 2; first_ = false; }                                           \
+                if (rem_ >= 1) {                                                           \
+                    if (first_) { CALL(1, true, part_); } else { CALL(1, false, part_); }  \
+                    rem_ -= 1; }                                                           \
+            }                                                                              \
+            _Pragma("unroll")                                                              \
+            for (int q_ = 0; q_ < VEC_; ++q_)                                              \
+                total.a[q_] = first_block_ ? part_.a[q_] : total.a[q_] + part_.a[q_];      \
+            first_block_ = false;                                                          \
+        }                                                                                  \
     } while (0)
 
 template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, int NT, int MODE, int BMAX>
@@ -145,16 +180,16 @@ __global__ __launch_bounds__(64) void se_step_kernel(const StepArgs p)
     uint64_t todo = members;
 
     if constexpr (MODE == kSesgd) {
-#define SE_CALL(B, F) sesgd_batch<VEC, BF16, HAS_V, HAS_WD, NT, B, F>(p, todo, off, goff, gpitch_bytes, s)
-        SE_FOR_MEMBER_BATCHES(BMAX, p.m, SE_CALL);
+#define SE_CALL(B, F, ACC) sesgd_batch<VEC, BF16, HAS_V, HAS_WD, NT, B, F>(p, todo, off, goff, gpitch_bytes, ACC)
+        SE_SUM_MEMBER_BLOCKS(BMAX, p.m, VEC, s, SE_CALL);
 #undef SE_CALL
     } else if constexpr (MODE == kGradAvg) {
-#define SE_CALL(B, F) sum_batch<VEC, BF16, NT, false, B, F>(p, todo, goff, gpitch_bytes, s)
-        SE_FOR_MEMBER_BATCHES(8, p.m, SE_CALL);
+#define SE_CALL(B, F, ACC) sum_batch<VEC, BF16, NT, false, B, F>(p, todo, goff, gpitch_bytes, ACC)
+        SE_SUM_MEMBER_BLOCKS(8, p.m, VEC, s, SE_CALL);
 #undef SE_CALL
     } else {
-#define SE_CALL(B, F) sum_batch<VEC, false, NT, true, B, F>(p, todo, off, p.pitch_bytes, s)
-        SE_FOR_MEMBER_BATCHES(8, p.m, SE_CALL);
+#define SE_CALL(B, F, ACC) sum_batch<VEC, false, NT, true, B, F>(p, todo, off, p.pitch_bytes, ACC)
+        SE_SUM_MEMBER_BLOCKS(8, p.m, VEC, s, SE_CALL);
 #undef SE_CALL
     }
 

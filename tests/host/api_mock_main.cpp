@@ -38,8 +38,8 @@ hipError_t record(const se::StepArgs &a, const se::LaunchShape &s, bool coop)
     EXPECT(a.inv_m == 1.0f / (float)a.m);
     EXPECT(s.lds_bytes <= se::kLdsPerCu);
     if (coop) {
-        EXPECT((size_t)a.m * 64 * s.vec * 4 <= 64u * 1024u);               // staging fits
-        EXPECT((a.m + 3) / 4 <= 16);                                       // <= 1024 threads
+        EXPECT((size_t)((a.m + 7) / 8) * 64 * s.vec * 4 <= 8u * 1024u);    // one staged block sum per wavefront
+        EXPECT((a.m + 7) / 8 <= 8);                                        // <= 512 threads
         EXPECT(a.coop_tiles >= 1);
     }
     // what the launch touches: the columns behind the leading, switched-off lanes
