@@ -65,9 +65,24 @@ extern "C" {
  *   group_of [host, n ints, out]           group index in [0, n/group_size) of each worker
  *   members  [host, n ints, out, may be NULL] group-major; members[g*group_size + r] is the
  *                                           r-th smallest worker id of group g
- * Runs the device generator on the current device, synchronously (default stream).
+ * Runs the device generator on the current device, synchronously (default stream).  Allocates
+ * and frees a small device buffer on every call (the free synchronises the device): meant for
+ * tests and set-up code; inside a training loop use se_plan_device or se_plan_noalloc.
  */
 int se_plan(int n, int group_size, int64_t iter, int32_t *group_of, int32_t *members);
+
+/*
+ * se_plan for callers that cannot allocate device memory (code that must not call hipMalloc:
+ * tight serving loops, harnesses that forbid it, set-up code next to a stream capture).  Same
+ * arguments, same results and same error codes as se_plan, but the device-side staging of the
+ * two result arrays lives in a 512-byte array that is part of the library's code object (one
+ * copy per GPU, kept until the process ends) instead of a buffer allocated and freed per call.
+ * Calls no hipMalloc / hipFree.  Limit: n <= SE_MAX_WORKERS (64); a larger n returns
+ * SE_ERR_UNSUPPORTED and touches nothing.  Synchronous, default stream, current device.  All
+ * calls on one GPU share that array: calls that overlap in time on the same GPU (from several
+ * threads or processes' streams) race and must be serialised by the caller.
+ */
+int se_plan_noalloc(int n, int group_size, int64_t iter, int32_t *group_of, int32_t *members);
 
 /* Same, asynchronous: both outputs are DEVICE arrays of n ints written on `stream`
  * (members_dev may be NULL).  Allocates nothing. */

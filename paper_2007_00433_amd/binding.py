@@ -25,7 +25,7 @@ SE_ERR_UNSUPPORTED = -5
 SE_ERR_HIP = -6
 SE_MAX_WORKERS = 64
 
-EXPORTS = ("se_plan", "se_plan_device", "se_step", "se_step_bf16g", "se_ring_step",
+EXPORTS = ("se_plan", "se_plan_noalloc", "se_plan_device", "se_step", "se_step_bf16g", "se_ring_step",
            "se_ring_step_bf16g", "se_set_seed", "se_get_seed", "se_pitch", "se_step_bytes",
            "se_set_tuning", "se_get_tuning", "se_strerror", "se_last_error", "se_calib_copy",
            "se_step_ex", "se_global_average", "se_consensus", "se_comm_model")
@@ -58,6 +58,8 @@ def _load() -> ctypes.CDLL:
     vp, f32, cp = ctypes.c_void_p, ctypes.c_float, ctypes.c_char_p
     lib.se_plan.restype = i32
     lib.se_plan.argtypes = [i32, i32, i64, vp, vp]
+    lib.se_plan_noalloc.restype = i32
+    lib.se_plan_noalloc.argtypes = [i32, i32, i64, vp, vp]
     lib.se_plan_device.restype = i32
     lib.se_plan_device.argtypes = [i32, i32, i64, vp, vp, vp]
     for name in ("se_step", "se_step_bf16g"):
@@ -210,6 +212,21 @@ def se_plan(n: int, group_size: int, it: int, want_members: bool = True):
     if want_members:
         return group_of[:n], members[:n].reshape(n // group_size, group_size)
     return group_of[:n], None
+
+
+def se_plan_noalloc(n: int, group_size: int, it: int, want_members: bool = True):
+    """se_plan through the entry point that allocates no device memory."""
+    group_of = np.full(max(n, 1), -1, np.int32)
+    members = np.full(max(n, 1), -1, np.int32) if want_members else None
+    check(lib.se_plan_noalloc(n, group_size, it, group_of.ctypes.data,
+                              members.ctypes.data if want_members else None))
+    if want_members:
+        return group_of[:n], members[:n].reshape(n // group_size, group_size)
+    return group_of[:n], None
+
+
+def se_plan_noalloc_raw(n, group_size, it, group_of_ptr, members_ptr) -> int:
+    return int(lib.se_plan_noalloc(n, group_size, it, group_of_ptr, members_ptr))
 
 
 def se_plan_device(n: int, group_size: int, it: int, group_of_dev, members_dev=None, stream=None):

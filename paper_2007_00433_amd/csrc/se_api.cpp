@@ -235,6 +235,14 @@ int se_plan(int n, int group_size, int64_t iter, int32_t *group_of, int32_t *mem
     return SE_OK;
 }
 
+int se_plan_noalloc(int n, int group_size, int64_t iter, int32_t *group_of, int32_t *members)
+{
+    const int rc = plan_check(n, group_size, iter, group_of);      // n > 64 is SE_ERR_UNSUPPORTED
+    if (rc != SE_OK) return rc;
+    const hipError_t e = se::plan_to_host_noalloc(g_seed.load(), iter, n, group_size, group_of, members);
+    return e == hipSuccess ? SE_OK : hip_fail("se_plan_noalloc", e);
+}
+
 int se_plan_device(int n, int group_size, int64_t iter, int32_t *group_of_dev,
                    int32_t *members_dev, void *stream)
 {

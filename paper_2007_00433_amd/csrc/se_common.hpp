@@ -48,11 +48,15 @@ struct LaunchShape {
 
 // single-wavefront form: grid (a.tiles, a.k)
 hipError_t launch_step(const StepArgs &a, const LaunchShape &s, hipStream_t stream);
-// cooperative form: a.m rows reduced together by ceil(a.m / 4) wavefronts per workgroup,
+// cooperative form: a.m rows reduced together by ceil(a.m / 8) wavefronts per workgroup,
 // grid (ceil(a.tiles / a.coop_tiles), a.k)
 hipError_t launch_coop(const StepArgs &a, const LaunchShape &s, hipStream_t stream);
 hipError_t launch_plan(uint64_t seed, int64_t iter, int n, int m, int32_t *group_of_dev,
                        int32_t *members_dev, hipStream_t stream);
+// regrouping staged in the library's own file-scope device array (no allocation), results copied
+// to host arrays of n ints; synchronous, default stream
+hipError_t plan_to_host_noalloc(uint64_t seed, int64_t iter, int n, int m, int32_t *group_of_host,
+                                int32_t *members_host);
 hipError_t launch_consensus(const float *x, uint64_t pitch_elems, uint64_t ncols, int n,
                             double *out_dev, hipStream_t stream);
 hipError_t launch_calib_copy(void *dst, const void *src, uint64_t nbytes, int policy,

@@ -3,6 +3,8 @@
 // worker; the same device function is what the step kernel evaluates in every wavefront.
 #include "se_device.hpp"
 
+#include <atomic>
+
 namespace se {
 
 __global__ __launch_bounds__(64) void se_plan_kernel(uint64_t seed, int64_t iter, int n, int m,
@@ -22,6 +24,52 @@ __global__ __launch_bounds__(64) void se_plan_kernel(uint64_t seed, int64_t iter
             }
         }
     }
+}
+
+// ---- the regrouping without any allocation ---------------------------------------------------
+// For callers that may not allocate device memory: the two result arrays are staged in a
+// file-scope device array instead of a buffer from hipMalloc.  `scratch` names the array on the
+// device; in host code the name is only a handle, so its device address is looked up once per
+// device with hipGetSymbolAddress and that address is what the kernel and the copies are given.
+constexpr int kPlanScratchInts = 2 * kMaxWorkers;          // group_of[64] then members[64]: 512 B
+static __device__ __align__(256) int32_t scratch[kPlanScratchInts];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<int32_t *> g_scratch_addr[kMaxDevices];   // per device ordinal; null = not looked up
+
+static hipError_t scratch_of_current_device(int32_t **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    int32_t *addr = g_scratch_addr[dev].load();
+    if (!addr) {
+        e = hipGetSymbolAddress((void **)&addr, HIP_SYMBOL(scratch));   // this device's copy
+        if (e != hipSuccess) return e;
+        if (!addr) return hipErrorInvalidSymbol;
+        g_scratch_addr[dev].store(addr);
+    }
+    *out = addr;
+    return hipSuccess;
+}
+
+hipError_t plan_to_host_noalloc(uint64_t seed, int64_t iter, int n, int m, int32_t *group_of_host,
+                                int32_t *members_host)
+{
+    if (n < 1 || n > kMaxWorkers) return hipErrorInvalidValue;     // the array holds 64 workers
+    int32_t *dev = nullptr;
+    hipError_t e = scratch_of_current_device(&dev);
+    if (e != hipSuccess) return e;
+    // every entry that is copied back is written by the kernel first: nothing to clear
+    hipLaunchKernelGGL(se_plan_kernel, dim3(1), dim3(64), 0, nullptr, seed, iter, n, m, dev,
+                       members_host ? dev + kMaxWorkers : nullptr);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = hipMemcpy(group_of_host, dev, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToHost);
+    if (e == hipSuccess && members_host)
+        e = hipMemcpy(members_host, dev + kMaxWorkers, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToHost);
+    return e;
 }
 
 hipError_t launch_plan(uint64_t seed, int64_t iter, int n, int m, int32_t *group_of_dev,

@@ -56,6 +56,7 @@ namespace se {
 hipError_t launch_step(const StepArgs &a, const LaunchShape &s, hipStream_t) { return record(a, s, false); }
 hipError_t launch_coop(const StepArgs &a, const LaunchShape &s, hipStream_t) { return record(a, s, true); }
 hipError_t launch_plan(uint64_t, int64_t, int, int, int32_t *, int32_t *, hipStream_t) { return hipSuccess; }
+hipError_t plan_to_host_noalloc(uint64_t, int64_t, int, int, int32_t *, int32_t *) { return hipSuccess; }
 hipError_t launch_consensus(const float *, uint64_t, uint64_t, int, double *, hipStream_t) { return hipSuccess; }
 hipError_t launch_calib_copy(void *, const void *, uint64_t, int, hipStream_t) { return hipSuccess; }
 }  // namespace se
