@@ -258,7 +258,7 @@ def main():
                    "pitch": pitch, "lr": w.lr, "momentum": w.mu, "grad_dtype": w.grad_dtype,
                    "grad_buffers_cycled": len(pool),
                    "tuning": {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}},
-        "roofline": {"bound": "hbm", "kernel": "se_coop_kernel" if se.se_get_tuning("cooperative") == 1 or (se.se_get_tuning("cooperative") < 0 and 8 <= m < 16) else "se_step_kernel", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": "se_coop_kernel" if se.se_get_tuning("cooperative") == 1 else "se_step_kernel", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "bytes_per_launch": bytes_per_launch,
                      "avg_launch_ms": round(per_launch * 1e3, 5),

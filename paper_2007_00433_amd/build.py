@@ -15,7 +15,7 @@ from concurrent.futures import ThreadPoolExecutor
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsesgd.so")
-SOURCES = ["se_api.cpp", "se_plan.hip", "se_step.hip", "se_coop.hip", "se_consensus.hip",
+SOURCES = ["se_api.cpp", "se_plan.hip", "se_step.hip", "se_coop.hip", "se_split.hip", "se_consensus.hip",
            "se_calib.hip"]
 
 HIP_FLAGS = [

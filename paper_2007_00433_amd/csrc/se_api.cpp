@@ -15,9 +15,15 @@ namespace {
 std::atomic<uint64_t> g_seed{0};
 std::atomic<int> g_nontemporal{2};         // se::Policy of the row accesses of launches that stream from HBM
 std::atomic<int> g_max_blocks_per_cu{-1}; // resident workgroups per CU (0 = no cap, -1 = chosen per launch)
-std::atomic<int> g_cooperative{-1};       // LDS-staged form: 0 never, 1 always, -1 where it measured faster
+std::atomic<int> g_cooperative{0};        // LDS-staged form: 0 never, 1 always (and no split form then)
 std::atomic<int> g_coop_tiles{0};         // cooperative form: consecutive tiles per workgroup (0 = by group size)
 std::atomic<int> g_cache_resident_mib{192};  // launches moving fewer MiB stay in the 256 MiB Infinity Cache
+std::atomic<int> g_split{-1};             // split form for more than 8 rows per group: 0 never, 1 always, -1 where it measured faster
+std::atomic<int> g_split_scratch_mib{128}; // size of the split form's intermediate buffer
+std::atomic<int> g_split_sub_tiles{4096}; // tiles per sub-chunk of the split form's finish launch
+std::atomic<int> g_split_cap_reduce{-1};  // resident workgroups per CU of the two launches (0 = no cap, -1 = default)
+std::atomic<int> g_split_cap_finish{-1};
+std::atomic<int> g_split_finish_rows{0};  // rows per wavefront of the finish launch (0 = default)
 
 thread_local char t_last_error[256] = "";
 
@@ -142,15 +148,56 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     const uint64_t moved = (uint64_t)j.n * (uint64_t)j.pitch * per_elem;
     const bool streams = moved >= ((uint64_t)g_cache_resident_mib.load() << 20);
     s.policy = streams ? g_nontemporal.load() : se::kPlain;
-    // The LDS-staged form measured 1-3 % faster for the SESGD update with 8 to 15 rows per
-    // group and slower or equal everywhere else (larger groups, the ring, the global average).
+    // The LDS-staged form (one block of 8 rows per wavefront, block sums staged in LDS) measured
+    // slower than the single-wavefront form for every group size (0.5-7 %) and than the split
+    // form for large ones; it runs only when asked for.
     const int coop = g_cooperative.load();
-    const bool use_coop = coop > 0 || (coop < 0 && j.mode == se::kSesgd && j.m >= 8 && j.m < 16);
+    const bool use_coop = coop > 0;
     int cap = streams ? g_max_blocks_per_cu.load() : 0;
-    if (cap < 0) cap = use_coop ? 6 : auto_blocks_per_cu(j, vec);
-    // the cooperative SESGD update measured 1-3 % faster with two more resident workgroups
-    if (use_coop && j.mode == se::kSesgd && cap > 0) cap += 2;
+    if (cap < 0) cap = use_coop ? 8 : auto_blocks_per_cu(j, vec);
     s.lds_bytes = cap > 0 ? (se::kLdsPerCu / (uint32_t)cap) & ~1023u : 0u;
+    // Split form: two launches per chunk of columns with an intermediate in a library-owned
+    // buffer; for reductions over more than 8 rows on the 128-bit path.  Measured on MI355X it
+    // beats the one-launch forms by 6-20 % for the gradient-averaging modes (the Ring-SGD
+    // baseline) and the SESGD update once a launch moves about a GiB, and it does not depend on
+    // where the driver happened to place the buffers; the parameter average alone is faster in
+    // one launch.
+    const int split = g_split.load();
+    const bool split_pays = j.mode != se::kAvgOnly &&
+                            (uint64_t)j.n * (uint64_t)(c1 - c0) * per_elem >= ((uint64_t)1 << 30);
+    if (vec == 4 && streams && j.m > (int)se::kSumBlockHost && coop <= 0 &&
+        (split > 0 || (split < 0 && split_pays))) {
+        const uint32_t nb = ((uint32_t)j.m + se::kSumBlockHost - 1u) / se::kSumBlockHost;
+        const uint32_t slots = j.mode == se::kGradAvg ? (uint32_t)a.k : (uint32_t)a.k * nb;
+        se::SplitShape sh;
+        sh.sub_tiles = (uint32_t)g_split_sub_tiles.load() / 8u * 8u;
+        const uint64_t budget = (uint64_t)g_split_scratch_mib.load() << 20;
+        uint64_t chunk = budget / ((uint64_t)slots * 1024u);            // 1 KiB per slot and tile
+        const uint64_t all = ((uint64_t)a.tiles + 7u) / 8u * 8u;
+        if (chunk > all) chunk = all;
+        if (chunk < sh.sub_tiles) sh.sub_tiles = (uint32_t)(chunk / 8u * 8u);
+        if (sh.sub_tiles >= 8u) {
+            chunk = chunk / sh.sub_tiles * sh.sub_tiles;
+            sh.chunk_tiles = (uint32_t)chunk;
+            sh.scratch = se::split_scratch(j.stream, (size_t)(chunk * slots * 1024u));
+            if (sh.scratch) {
+                int fr = g_split_finish_rows.load();
+                if (j.mode == se::kGradAvg) fr = fr >= 4 ? 4 : fr >= 2 ? 2 : 1;
+                else fr = fr < 8 ? 8 : fr / 8 * 8;
+                sh.finish_rows = fr;
+                // Resident workgroups per CU, from sweeps on the ResNet-50, VGG-16 and BERT shapes:
+                // the mean-gradient pass has 8 KiB or less in flight per wavefront and wants 12 or
+                // more, the one-row update 24; the 8-row SESGD pass 4 (6 with bf16 gradients),
+                // the pass that writes the mean 16.
+                int cr = g_split_cap_reduce.load(), cf = g_split_cap_finish.load();
+                if (cr < 0) cr = j.mode == se::kGradAvg ? 12 : j.grad_bytes == 2 ? 6 : 4;
+                if (cf < 0) cf = j.mode == se::kGradAvg ? 24 : 16;
+                sh.lds_reduce = cr > 0 ? (se::kLdsPerCu / (uint32_t)cr) & ~1023u : 0u;
+                sh.lds_finish = cf > 0 ? (se::kLdsPerCu / (uint32_t)cf) & ~1023u : 0u;
+                return se::launch_split(a, s, sh, j.stream);
+            }
+        }
+    }
     if (use_coop) return se::launch_coop(a, s, j.stream);
     return se::launch_step(a, s, j.stream);
 }
@@ -209,9 +256,15 @@ struct Knob { const char *name; std::atomic<int> *value; int lo, hi; };
 Knob kKnobs[] = {
     {"max_blocks_per_cu", &g_max_blocks_per_cu, -1, 32},
     {"nontemporal", &g_nontemporal, 0, 2},
-    {"cooperative", &g_cooperative, -1, 1},
+    {"cooperative", &g_cooperative, 0, 1},
     {"coop_tiles", &g_coop_tiles, 0, 4096},
     {"cache_resident_mib", &g_cache_resident_mib, 0, 1 << 20},
+    {"split", &g_split, -1, 1},
+    {"split_scratch_mib", &g_split_scratch_mib, 1, 4096},
+    {"split_sub_tiles", &g_split_sub_tiles, 8, 1 << 24},
+    {"split_cap_reduce", &g_split_cap_reduce, -1, 32},
+    {"split_cap_finish", &g_split_cap_finish, -1, 32},
+    {"split_finish_rows", &g_split_finish_rows, 0, 64},
 };
 
 }  // namespace

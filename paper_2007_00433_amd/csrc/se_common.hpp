@@ -11,6 +11,7 @@ namespace se {
 
 constexpr int kMaxWorkers = 64;              // one lane per worker in the plan generator
 constexpr uint32_t kLdsPerCu = 160 * 1024;   // gfx950 LDS per compute unit
+constexpr uint32_t kSumBlockHost = 8;        // members per block of the summation order
 
 // What a step kernel computes per group (see se_step.hip for the passages).
 enum Mode : int { kSesgd = 0, kGradAvg = 1, kAvgOnly = 2 };
@@ -46,11 +47,27 @@ struct LaunchShape {
     uint32_t lds_bytes;     // dynamic LDS requested only to cap resident workgroups per CU
 };
 
+// Split form: what the host decides per call.
+struct SplitShape {
+    float *scratch;         // library-owned device buffer of slots * chunk_tiles * 1 KiB
+    uint32_t chunk_tiles;   // tiles per pair of launches
+    uint32_t sub_tiles;     // tiles per sub-chunk of the finish launch
+    int finish_rows;        // rows per wavefront of the finish launch: 1, 2, 4 when gradients are
+                            // averaged, a multiple of 8 otherwise
+    uint32_t lds_reduce;    // dynamic LDS of the two launches, only to cap residency (0 = none)
+    uint32_t lds_finish;
+};
+
 // single-wavefront form: grid (a.tiles, a.k)
 hipError_t launch_step(const StepArgs &a, const LaunchShape &s, hipStream_t stream);
 // cooperative form: a.m rows reduced together by ceil(a.m / 8) wavefronts per workgroup,
 // grid (ceil(a.tiles / a.coop_tiles), a.k)
 hipError_t launch_coop(const StepArgs &a, const LaunchShape &s, hipStream_t stream);
+// split form (128-bit path only): two launches per chunk of sh.chunk_tiles tiles
+hipError_t launch_split(const StepArgs &a, const LaunchShape &s, const SplitShape &sh, hipStream_t stream);
+// the split form's buffer for `stream` on the current device, at least `bytes` long; null when
+// none can be had (allocation failed, too many streams, or the stream is being captured)
+float *split_scratch(hipStream_t stream, size_t bytes);
 hipError_t launch_plan(uint64_t seed, int64_t iter, int n, int m, int32_t *group_of_dev,
                        int32_t *members_dev, hipStream_t stream);
 // regrouping staged in the library's own file-scope device array (no allocation), results copied

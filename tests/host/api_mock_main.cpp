@@ -55,6 +55,19 @@ hipError_t record(const se::StepArgs &a, const se::LaunchShape &s, bool coop)
 namespace se {
 hipError_t launch_step(const StepArgs &a, const LaunchShape &s, hipStream_t) { return record(a, s, false); }
 hipError_t launch_coop(const StepArgs &a, const LaunchShape &s, hipStream_t) { return record(a, s, true); }
+hipError_t launch_split(const StepArgs &a, const LaunchShape &s, const SplitShape &sh, hipStream_t)
+{
+    EXPECT(s.vec == 4 && a.m > 8 && sh.scratch != nullptr);
+    EXPECT(sh.sub_tiles >= 8 && sh.sub_tiles % 8 == 0 && sh.chunk_tiles >= sh.sub_tiles && sh.chunk_tiles % sh.sub_tiles == 0);
+    EXPECT(sh.lds_reduce <= se::kLdsPerCu && sh.lds_finish <= se::kLdsPerCu);
+    return record(a, s, false);
+}
+float *split_scratch(hipStream_t, size_t bytes)
+{
+    static float dummy;
+    EXPECT(bytes > 0 && bytes <= ((size_t)4096 << 20));
+    return &dummy;
+}
 hipError_t launch_plan(uint64_t, int64_t, int, int, int32_t *, int32_t *, hipStream_t) { return hipSuccess; }
 hipError_t plan_to_host_noalloc(uint64_t, int64_t, int, int, int32_t *, int32_t *) { return hipSuccess; }
 hipError_t launch_consensus(const float *, uint64_t, uint64_t, int, double *, hipStream_t) { return hipSuccess; }

@@ -353,7 +353,9 @@ def test_results_do_not_depend_on_launch_knobs_or_stream():
               dict(cache_resident_mib=0, cooperative=0),
               dict(cache_resident_mib=0, nontemporal=1), dict(cache_resident_mib=0, nontemporal=1, cooperative=1),
               dict(cooperative=1, coop_tiles=1), dict(cooperative=1, coop_tiles=7),
-              dict(cooperative=1, coop_tiles=4096)]
+              dict(cooperative=1, coop_tiles=4096),
+              dict(cache_resident_mib=0, split=1), dict(cache_resident_mib=0, split=1, split_scratch_mib=1, split_sub_tiles=8),
+              dict(cache_resident_mib=0, split=1, split_cap_reduce=0, split_cap_finish=2)]
     defaults = {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}
     for q, shape in enumerate(shapes):
         for k, val in {**defaults, **shape}.items():
@@ -395,6 +397,50 @@ def test_both_kernel_forms_for_every_group_size(coop):
         case = Case(n, ncols, dtype=dtype, use_v=(n % 2 == 0), v_std=0.0)
         run_ring(case, 2, 0.1, 0.9 if n % 2 == 0 else 0.0, 1e-2)
         case.check(f"coop={coop} ring n={n} cols={ncols} {dtype}")
+
+
+@pytest.mark.parametrize("sub_tiles", [8, 64])
+def test_split_form_for_large_groups(sub_tiles, always_streaming):
+    """The two-launch form (block sums / mean gradients handed over through the library's own
+    buffer) against the oracle: several chunks (1 MiB buffer), ragged last chunk and sub-chunk,
+    ragged last block of a group (12 = 8 + 4, 20 = 8 + 8 + 4), all three modes, layer ranges
+    that start inside a 1 KiB piece, a side stream."""
+    se.se_set_tuning("split", 1)
+    se.se_set_tuning("split_scratch_mib", 1)
+    se.se_set_tuning("split_sub_tiles", sub_tiles)
+    side = torch.cuda.Stream()
+    for n, m, ncols, dtype in [(64, 64, 160000, "bf16"), (64, 16, 66000, "f32"), (24, 12, 90004, "f32"),
+                               (40, 20, 70000, "bf16"), (9, 9, 300000, "f32"), (32, 32, 4, "f32")]:
+        what = f"split sub={sub_tiles} n={n} m={m} cols={ncols} {dtype}"
+        say(what)
+        case = Case(n, ncols, dtype=dtype, distinct_rows=True, v_std=0.01)
+        run_sesgd(case, m, 2, 0.1, 0.9, 1e-2)
+        case.check(what + " step")
+        run_ring(case, 2, 0.1, 0.9, 1e-2, stream=side)
+        side.synchronize()
+        case.check(what + " ring")
+        offs = case.offsets()
+        hg = case.grads(7, 1e-2)
+        se.se_step_ex(case.dx, case.dg, case.dv, offs, n, m, 7, 0.1, 0.9, 5e-4, GA, grads_are_bf16=(dtype == "bf16"))
+        oracle.step_ex(case.hx, hg, case.hv, m, 7, 0.1, 0.9, 5e-4, oracle.FLAG_GRAD_AVG)
+        se.se_step_ex(case.dx, case.dg, case.dv, offs, n, m, 8, 0.1, 0.9, 5e-4, 0, grads_are_bf16=(dtype == "bf16"))
+        oracle.step_ex(case.hx, hg, case.hv, m, 8, 0.1, 0.9, 5e-4, 0)
+        case.check(what + " decay, both modes")
+        se.se_global_average(case.dx, offs, n)
+        oracle.global_average(case.hx)
+        case.check(what + " global average")
+    # no momentum buffer, and layer ranges off the 1 KiB grid
+    sizes = [1000, 40000, 24, 30000, 4]
+    n, m = 32, 16
+    case = Case(n, sum(sizes), use_v=False, distinct_rows=True)
+    offs = case.offsets(sizes)
+    hg = case.grads(0, 1e-2)
+    for first, last in [(3, 5), (0, 1), (1, 3)]:
+        se.se_step_ex(case.dx, case.dg, None, offs, n, m, 3, 0.1, 0.0, 0.0, 0, first_layer=first, last_layer=last)
+        se.se_step_ex(case.dx, case.dg, None, offs, n, n, 3, 0.1, 0.0, 0.0, GA, first_layer=first, last_layer=last)
+    oracle.step_ex(case.hx, hg, None, m, 3, 0.1, 0.0, 0.0, 0)
+    oracle.step_ex(case.hx, hg, None, n, 3, 0.1, 0.0, 0.0, oracle.FLAG_GRAD_AVG)
+    case.check("split: layer ranges, no momentum")
 
 
 def test_steps_captured_in_a_graph_replay_correctly():
@@ -536,7 +582,7 @@ def test_full_size_resnet50_other_group_sizes_sampled(group_size):
 GA = se.SE_FLAG_GRAD_AVG
 
 
-@pytest.mark.parametrize("coop", [0, 1, -1])
+@pytest.mark.parametrize("coop", [0, 1])
 def test_step_ex_weight_decay_and_gradient_averaging(coop):
     se.se_set_tuning("cooperative", coop)
     for n, m, ncols, dtype, wd, flags in [(16, 4, 1029, "f32", 5e-4, 0), (16, 4, 1029, "f32", 1e-4, GA),
@@ -730,9 +776,11 @@ def test_randomised_configurations():
         wd = float(rng.choice([0.0, 1e-4, 5e-4]))
         flags = GA if rng.integers(0, 3) == 0 else 0
         shift = int(rng.choice([0, 0, 1, 2, 4]))
-        knobs = dict(cooperative=int(rng.choice([-1, 0, 1])), nontemporal=int(rng.integers(0, 3)),
+        knobs = dict(cooperative=int(rng.choice([0, 0, 1])), nontemporal=int(rng.integers(0, 3)),
                      coop_tiles=int(rng.choice([1, 2, 4, 5, 64])),
-                     max_blocks_per_cu=int(rng.choice([-1, 0, 1, 6, 32])), cache_resident_mib=int(rng.choice([0, 192])))
+                     max_blocks_per_cu=int(rng.choice([-1, 0, 1, 6, 32])), cache_resident_mib=int(rng.choice([0, 192])),
+                     split=int(rng.choice([-1, 0, 1])), split_sub_tiles=int(rng.choice([8, 512])),
+                     split_scratch_mib=int(rng.choice([1, 64])))
         for k, val in {**defaults, **knobs}.items():
             se.se_set_tuning(k, val)
         se.se_set_seed(int(rng.integers(0, 2 ** 63)))
