@@ -36,6 +36,12 @@ def parse():
     ap.add_argument("--skip-copy", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=3.0, help="target CPU time per oracle leg")
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE")
+    ap.add_argument("--reallocs", type=int, default=8,
+                    help="after the headline region: free and re-allocate the buffers this many times "
+                         "and time se_step / se_ring_step on each placement (0 = skip)")
+    ap.add_argument("--call-all", action="store_true",
+                    help="instead of the benchmark: call every device entry point a few times on the "
+                         "workload's buffers and print one line per call (a dispatch list for profilers)")
     ap.add_argument("--all-workloads", action="store_true",
                     help="also time se_step / se_ring_step / the oracle on every configured workload "
                          "(reported under 'all_workloads'; the headline fields are unchanged)")
@@ -178,6 +184,76 @@ def measure_workload(name, steps, warmup, cpu_seconds, torch, se, wl):
     return res
 
 
+def call_all(w, torch, se, reps=3):
+    """Every device entry point on buffers of one shape, so that a profiler run shows their
+    counters side by side.  One line per call with its mean time from stream events."""
+    n, m, P = w.n, w.group_size, w.P
+    pitch = se.se_pitch(P)
+    offs = w.layer_offsets(pitch)
+    bf16 = w.grad_dtype == "bf16"
+    x = torch.randn(n, pitch, device="cuda") * w.param_std
+    v = torch.zeros(n, pitch, device="cuda")
+    g = (torch.randn(n, pitch, device="cuda") * w.grad_std).to(torch.bfloat16 if bf16 else torch.float32)
+    out = torch.zeros(2, dtype=torch.float64, device="cuda")
+    step = se.se_step_bf16g if bf16 else se.se_step
+    ring = se.se_ring_step_bf16g if bf16 else se.se_ring_step
+    calls = [
+        ("se_step", lambda t: step(x, g, v, offs, n, m, t, w.lr, 0.9), 16 + w.grad_bytes),
+        ("se_step, one group", lambda t: step(x, g, v, offs, n, n, t, w.lr, 0.9), 16 + w.grad_bytes),
+        ("se_ring_step", lambda t: ring(x, g, v, offs, n, w.lr, 0.9), 16 + w.grad_bytes),
+        ("se_ring_step, no momentum", lambda t: ring(x, g, None, offs, n, w.lr, 0.0), 8 + w.grad_bytes),
+        ("se_global_average", lambda t: se.se_global_average(x, offs, n), 8),
+        ("se_consensus", lambda t: se.se_consensus(x, offs, n, out), 4),
+    ]
+    stream = torch.cuda.current_stream()
+    for name, call, bytes_per_element in calls:
+        call(0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for t in range(1, 1 + reps):
+            call(t)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        print(f"{name:28s} {ms:9.3f} ms  {n * P * bytes_per_element / ms / 1e6:8.1f} GB/s", flush=True)
+
+
+def realloc_spread(w, pitch, offs, count, steps, torch, se):
+    """The same binary and inputs run at different speeds depending on where the driver places
+    the buffers.  Frees and re-allocates params, momentum and one gradient buffer `count` times
+    (the caching allocator is emptied in between, so every round is a fresh hipMalloc) and times
+    se_step and se_ring_step on each placement."""
+    n, m, P = w.n, w.group_size, w.P
+    bf16 = w.grad_dtype == "bf16"
+    step_fn = se.se_step_bf16g if bf16 else se.se_step
+    ring_fn = se.se_ring_step_bf16g if bf16 else se.se_ring_step
+    nbytes = se.se_step_bytes(P, n, w.grad_bytes, True)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    step_gbs, ring_gbs = [], []
+    for _ in range(count):
+        torch.cuda.empty_cache()
+        x = torch.zeros(n, pitch, device="cuda")
+        x[:, :P] = torch.randn(P, device="cuda", generator=gen) * w.param_std
+        v = torch.zeros(n, pitch, device="cuda")
+        g = torch.zeros(n, pitch, device="cuda", dtype=torch.bfloat16 if bf16 else torch.float32)
+        for i in range(n):
+            g[i, :P] = (torch.randn(P, device="cuda", generator=gen) * w.grad_std).to(g.dtype)
+        _, per = timed_steps(lambda t, s: step_fn(x, g, v, offs, n, m, t, w.lr, w.mu, s), steps, 3, torch)
+        _, rper = timed_steps(lambda t, s: ring_fn(x, g, v, offs, n, w.lr, w.mu, s), steps, 3, torch)
+        step_gbs.append(nbytes / per / 1e9)
+        ring_gbs.append(nbytes / rper / 1e9)
+        del x, v, g
+    torch.cuda.empty_cache()
+
+    def summary(vals):
+        vals = sorted(vals)
+        return {"min": round(vals[0], 1), "median": round(vals[len(vals) // 2], 1),
+                "max": round(vals[-1], 1), "count": len(vals)}
+    return summary(step_gbs), summary(ring_gbs)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -198,6 +274,9 @@ def main():
         se.se_set_tuning(name, int(value))
 
     w = wl.WORKLOADS[args.workload]
+    if args.call_all:
+        call_all(w, torch, se)
+        return
     n, m, P = w.n, w.group_size, w.P
     pitch = P if args.no_pad else se.se_pitch(P)
     offs = w.layer_offsets(pitch)
@@ -230,17 +309,21 @@ def main():
     # spread of single launches, outside the timed region: median and fastest of the same count
     each = per_launch_ms(launch_step, args.steps, args.warmup + args.steps, torch)
 
-    # HBM bytes per launch measured offline with rocprofv3 --pmc: the `sesgd` row of the traffic
+    # HBM bytes per launch measured offline with rocprofv3 --pmc: the `se_step` row of the traffic
     # table in profiles/se_step_<workload>_n<n>_m<m>.md (written by profile_summary.py)
     traffic = None
     prof = os.path.join(ROOT, "profiles", f"se_step_{args.workload}_n{n}_m{m}.md")
+    traffic_source = None
     if os.path.exists(prof):
+        traffic_source = (f"profiles/{os.path.basename(prof)}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of "
+                          "this program, scaled by the plain copy kernel; measured in separate, earlier "
+                          "processes, not in this run")
         with open(prof) as f:
             text = f.read()
         if f"pitch={pitch})" in text:
             for line in text.splitlines():
                 cells = [c.strip() for c in line.split("|")]
-                if len(cells) == 10 and cells[1] == "sesgd" and cells[6].isdigit():
+                if len(cells) == 10 and cells[1] == "se_step" and cells[6].isdigit():
                     traffic = int(cells[6])
 
     out = {
@@ -260,7 +343,8 @@ def main():
                    "tuning": {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}},
         "roofline": {"bound": "hbm", "kernel": "se_coop_kernel" if se.se_get_tuning("cooperative") == 1 else "se_step_kernel", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": traffic, "bytes_per_launch": bytes_per_launch,
+                     "traffic": traffic, "traffic_source": traffic_source if traffic else None,
+                     "bytes_per_launch": bytes_per_launch,
                      "avg_launch_ms": round(per_launch * 1e3, 5),
                      "median_launch_ms": round(each[len(each) // 2], 5),
                      "min_launch_ms": round(each[0], 5)},
@@ -294,8 +378,27 @@ def main():
                     "latency; cluster measurements, not comparable with a single-GPU step rate",
         "comm_model_1gbps_per_iteration": model,
     }
-    if not args.skip_cpu_baseline:
+    # how many times each entry point was called: lets a profiler's per-kernel totals of this
+    # run be turned into per-call figures
+    out["api_calls"] = {"se_step": args.warmup + 2 * args.steps,
+                        "se_ring_step": 0 if args.skip_ring else args.warmup + args.steps,
+                        "se_calib_copy": 0 if args.skip_copy or len(pool) < 2 else 3 + max(10, args.steps // 2)}
+    released = False
+    if args.reallocs > 0:
         del pool, x, v
+        released = True
+        rsteps = args.steps if bytes_per_launch < 2e10 else max(4, args.steps // 5)
+        srl, rrl = realloc_spread(w, pitch, offs, args.reallocs, rsteps, torch, se)
+        out["roofline"]["realloc_gbs"] = srl
+        out["roofline"]["realloc_frac_min"] = round(srl["min"] / HBM_PEAK_GBS, 4)
+        if "ring_baseline" in out:
+            out["ring_baseline"]["realloc_gbs"] = rrl
+        for key in ("se_step", "se_ring_step"):
+            out["api_calls"][key] += args.reallocs * (3 + rsteps)
+    if not args.skip_cpu_baseline:
+        if not released:
+            del pool, x, v
+            released = True
         torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(w, pitch, args.cpu_seconds)
     if args.all_workloads:
@@ -309,7 +412,7 @@ def main():
                 se.se_step_ex(x, pool[t % len(pool)], v, offs, n, m, t, w.lr, w.mu, 0.0, 0,
                               first_layer=l, last_layer=l + 1, grads_are_bf16=bf16, stream=stream)
 
-        if not args.skip_cpu_baseline:          # x, v, pool were released above
+        if released:                            # x, v, pool were released above
             x = torch.zeros(n, pitch, device="cuda")
             v = torch.zeros(n, pitch, device="cuda")
             pool = [torch.zeros(n, pitch, device="cuda", dtype=torch.bfloat16 if bf16 else torch.float32)]
@@ -335,10 +438,45 @@ def main():
                 stream.wait_event(end)
 
         swall, _ = timed_steps(launch_per_layer_streams, lsteps, 2, torch)
+        # The same 161 calls recorded once into a HIP graph and replayed: what the GPU needs for
+        # them without the per-call cost of the host (Python, argument checks, launch).
+        side = torch.cuda.Stream()
+        launch_per_layer(0, side)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            launch_per_layer(1, torch.cuda.current_stream())
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(lsteps):
+            graph.replay()
+        torch.cuda.synchronize()
+        gwall = time.perf_counter() - t0
+        del graph
+
+        # Buckets, as data-parallel frameworks cut their gradient exchange: consecutive tensors
+        # (back to front) are stepped together once they add up to 1 Mi elements or more.
+        buckets, hi, acc = [], L, 0
+        for l in range(L - 1, -1, -1):
+            acc += int(w.sizes[l])
+            if acc >= (1 << 20) or l == 0:
+                buckets.append((l, hi))
+                hi, acc = l, 0
+
+        def launch_buckets(t, stream):
+            for first, last in buckets:
+                se.se_step_ex(x, pool[t % len(pool)], v, offs, n, m, t, w.lr, w.mu, 0.0, 0,
+                              first_layer=first, last_layer=last, grads_are_bf16=bf16, stream=stream)
+
+        bwall, _ = timed_steps(launch_buckets, lsteps, 2, torch)
         out["per_layer_schedule"] = {"launch_calls_per_step": L,
                                      "steps_per_s": round(lsteps / lwall, 3),
                                      "fused_over_per_layer": round(out["value"] * lwall / lsteps, 3),
-                                     "steps_per_s_on_4_streams": round(lsteps / swall, 3)}
+                                     "steps_per_s_on_4_streams": round(lsteps / swall, 3),
+                                     "steps_per_s_replayed_from_a_graph": round(lsteps / gwall, 3),
+                                     "buckets_of_1Mi_elements": len(buckets),
+                                     "steps_per_s_in_buckets": round(lsteps / bwall, 3)}
         out["all_workloads"] = {}
         for name in ("tiny", "resnet20", "resnet50", "vgg16", "bert_base", "bert_base_full"):
             out["all_workloads"][name] = measure_workload(

@@ -1,0 +1,59 @@
+/*
+ * sesgd_tuning.h -- measurement and tuning entry points of libsesgd.so.  Not part of the
+ * method's boundary (that is sesgd.h): nothing here changes a result, only how the launches
+ * are shaped, and one helper gives the profiler's byte counters a known reference.
+ */
+#ifndef SESGD_TUNING_H
+#define SESGD_TUNING_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Measurement helper, not part of the method: copies nbytes (a multiple of 16, below 2^37)
+ * between two non-overlapping, 16-byte aligned DEVICE buffers with a plain streaming kernel
+ * on `stream`.  Reads nbytes and writes nbytes: the reference reading for the profiler's HBM
+ * byte counters and a practical bandwidth ceiling next to se_step's figure. */
+int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
+
+/* Launch-shape knobs for measurement sweeps; results never depend on them (process-wide).
+ *   "max_blocks_per_cu"   one-launch forms: cap on resident workgroups per compute unit, enforced
+ *                         by requesting 160 KiB / cap of (unused) LDS per workgroup; 0 = no cap;
+ *                         -1 (default) = the measured optimum per launch: 16, 12, 6 for group
+ *                         sizes 1, 2, 4 (about 72 KiB of loads in flight per compute unit), 4 up
+ *                         to 8 rows, 2 beyond, 2 for gradient averaging, 4 for the global
+ *                         average, 8 for the LDS-staged form
+ *   "nontemporal"         cache policy of the row accesses: 0 plain; 1 streaming (non-temporal)
+ *                         loads and stores; 2 (default) streaming, and stores written through
+ *                         the L2 to memory at once (measured 2-4 % faster than 1)
+ *   "cooperative"         1: LDS-staged form: every wavefront of a workgroup owns one block of 8
+ *                         rows of the group and stages its block sum in LDS; 0 (default): never
+ *                         (it measured 0.5-7 % slower than the single-wavefront form)
+ *   "coop_tiles"          LDS-staged form: consecutive 64-lane tiles one workgroup walks through;
+ *                         0 = chosen by group size: 4 above 32 rows, else 1 (default 0)
+ *   "cache_resident_mib"  when a full-range call would move fewer MiB than this (default 192;
+ *                         the Infinity Cache holds 256 MiB) launches use plain accesses and no
+ *                         residency cap, which is faster when nothing streams from HBM;
+ *                         0 = always stream
+ *   "split"               two-launch form for reductions over more than 8 rows (see sesgd.h,
+ *                         "Device memory of the library's own"): 1 whenever the 128-bit path
+ *                         applies, 0 never, -1 (default) when a launch moves 1 GiB or more and
+ *                         the mode is not the plain parameter average
+ *   "split_scratch_mib"   size of that form's buffer per (device, stream), default 128
+ *   "split_sub_tiles"     tiles of 64 lane-columns per sub-chunk of its second launch; 0 (default)
+ *                         = 4096 when gradients are averaged, 2048 otherwise
+ *   "split_cap_reduce", "split_cap_finish"   resident workgroups per compute unit of its first
+ *                         and second launch; 0 = no cap; -1 (default) = 12 and 24 when gradients
+ *                         are averaged, else 4 (6 with bf16 gradients) and 16
+ *   "split_finish_rows"   rows per wavefront of its second launch: 1, 2 or 4 when gradients are
+ *                         averaged, a multiple of 8 otherwise; 0 (default) = 1 and 8
+ * Returns SE_ERR_ARG for an unknown name or a value out of range. */
+int se_set_tuning(const char *name, int value);
+int se_get_tuning(const char *name);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SESGD_TUNING_H */

@@ -9,6 +9,7 @@
 #include <cstring>
 
 #include "../../include/sesgd.h"
+#include "../../include/sesgd_tuning.h"
 
 namespace {
 
@@ -20,7 +21,7 @@ std::atomic<int> g_coop_tiles{0};         // cooperative form: consecutive tiles
 std::atomic<int> g_cache_resident_mib{192};  // launches moving fewer MiB stay in the 256 MiB Infinity Cache
 std::atomic<int> g_split{-1};             // split form for more than 8 rows per group: 0 never, 1 always, -1 where it measured faster
 std::atomic<int> g_split_scratch_mib{128}; // size of the split form's intermediate buffer
-std::atomic<int> g_split_sub_tiles{4096}; // tiles per sub-chunk of the split form's finish launch
+std::atomic<int> g_split_sub_tiles{0};    // tiles per sub-chunk of the split form's finish launch (0 = by mode)
 std::atomic<int> g_split_cap_reduce{-1};  // resident workgroups per CU of the two launches (0 = no cap, -1 = default)
 std::atomic<int> g_split_cap_finish{-1};
 std::atomic<int> g_split_finish_rows{0};  // rows per wavefront of the finish launch (0 = default)
@@ -153,8 +154,8 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     // form for large ones; it runs only when asked for.
     const int coop = g_cooperative.load();
     const bool use_coop = coop > 0;
-    int cap = streams ? g_max_blocks_per_cu.load() : 0;
-    if (cap < 0) cap = use_coop ? 8 : auto_blocks_per_cu(j, vec);
+    int cap = g_max_blocks_per_cu.load();
+    if (cap < 0) cap = !streams ? 0 : use_coop ? 8 : auto_blocks_per_cu(j, vec);
     s.lds_bytes = cap > 0 ? (se::kLdsPerCu / (uint32_t)cap) & ~1023u : 0u;
     // Split form: two launches per chunk of columns with an intermediate in a library-owned
     // buffer; for reductions over more than 8 rows on the 128-bit path.  Measured on MI355X it
@@ -170,7 +171,10 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
         const uint32_t nb = ((uint32_t)j.m + se::kSumBlockHost - 1u) / se::kSumBlockHost;
         const uint32_t slots = j.mode == se::kGradAvg ? (uint32_t)a.k : (uint32_t)a.k * nb;
         se::SplitShape sh;
+        // Sub-chunks of 4096 tiles (4 MiB of every row) measured best when one mean gradient is
+        // re-read per row, 256-2048 tiles alike and 4096 5 % slower when 8 block sums are.
         sh.sub_tiles = (uint32_t)g_split_sub_tiles.load() / 8u * 8u;
+        if (sh.sub_tiles == 0) sh.sub_tiles = j.mode == se::kGradAvg ? 4096u : 2048u;
         const uint64_t budget = (uint64_t)g_split_scratch_mib.load() << 20;
         uint64_t chunk = budget / ((uint64_t)slots * 1024u);            // 1 KiB per slot and tile
         const uint64_t all = ((uint64_t)a.tiles + 7u) / 8u * 8u;
@@ -261,7 +265,7 @@ Knob kKnobs[] = {
     {"cache_resident_mib", &g_cache_resident_mib, 0, 1 << 20},
     {"split", &g_split, -1, 1},
     {"split_scratch_mib", &g_split_scratch_mib, 1, 4096},
-    {"split_sub_tiles", &g_split_sub_tiles, 8, 1 << 24},
+    {"split_sub_tiles", &g_split_sub_tiles, 0, 1 << 24},
     {"split_cap_reduce", &g_split_cap_reduce, -1, 32},
     {"split_cap_finish", &g_split_cap_finish, -1, 32},
     {"split_finish_rows", &g_split_finish_rows, 0, 64},

@@ -180,3 +180,18 @@ def sample_columns(pitch: int, count: int, seed: int = 0, tile: int = 1024) -> n
                             np.arange(pitch - tile, pitch)])
     rnd = _rng(seed, 0x5A3B).integers(0, pitch, size=max(count - fixed.size, 0))
     return np.unique(np.concatenate([fixed, rnd]).astype(np.int64))
+
+
+def stratified_columns(pitch: int, whole_tiles: int, random_count: int, seed: int = 0,
+                       tile: int = 256) -> np.ndarray:
+    """Sorted column sample made of whole tiles of ``tile`` columns (the first, the last, and
+    evenly spaced ones in between: ``whole_tiles`` in all) plus ``random_count`` uniformly random
+    columns.  256 fp32 columns are the 1 KiB piece of a row that one wavefront moves per access."""
+    ntiles = (pitch + tile - 1) // tile
+    if ntiles <= whole_tiles:
+        return np.arange(pitch, dtype=np.int64)
+    picks = np.unique(np.linspace(0, ntiles - 1, whole_tiles).astype(np.int64))
+    cols = (picks[:, None] * tile + np.arange(tile)[None, :]).reshape(-1)
+    cols = cols[cols < pitch]
+    rnd = _rng(seed, 0x57A7).integers(0, pitch, size=random_count)
+    return np.unique(np.concatenate([cols, rnd]).astype(np.int64))

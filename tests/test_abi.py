@@ -14,10 +14,13 @@ FAKE = 0x10000          # a non-NULL, 16-byte aligned address that is never dere
                         # every call below fails validation before any HIP call
 
 
-def header_symbols():
-    text = open(os.path.join(ROOT, "include", "sesgd.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(se_[a-z0-9_]+)\s*\(", text)))
+def header_symbols(names=("sesgd.h", "sesgd_tuning.h")):
+    found = set()
+    for name in names:
+        text = open(os.path.join(ROOT, "include", name)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        found |= set(re.findall(r"\b(se_[a-z0-9_]+)\s*\(", text))
+    return sorted(found)
 
 
 def test_library_exports_every_declared_symbol():
@@ -27,6 +30,10 @@ def test_library_exports_every_declared_symbol():
     for name in names:
         assert hasattr(lib, name), name
     assert sorted(se.EXPORTS) == names
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["sesgd.h", "sesgd_tuning.h"]
+    # the method's header carries no measurement scaffolding
+    assert header_symbols(("sesgd_tuning.h",)) == ["se_calib_copy", "se_get_tuning", "se_set_tuning"]
+    assert not set(header_symbols(("sesgd.h",))) & {"se_calib_copy", "se_get_tuning", "se_set_tuning"}
     for name in names:                      # the Python binding carries the same names
         assert hasattr(se, name), name
 
@@ -55,7 +62,7 @@ def test_seed_and_tuning_state():
     for name, good, bad in (("nontemporal", 0, 3),
                             ("max_blocks_per_cu", 2, 33), ("cooperative", 1, -1),
                             ("cache_resident_mib", 0, -1), ("coop_tiles", 3, -1),
-                            ("split", 0, 2), ("split_scratch_mib", 16, 0), ("split_sub_tiles", 64, 7),
+                            ("split", 0, 2), ("split_scratch_mib", 16, 0), ("split_sub_tiles", 64, -1),
                             ("split_cap_reduce", 3, 33), ("split_cap_finish", 0, -2),
                             ("split_finish_rows", 16, 65)):
         assert name in se.TUNING_KNOBS
