@@ -33,7 +33,7 @@ int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
  *                         (it measured 0.5-7 % slower than the single-wavefront form)
  *   "coop_tiles"          LDS-staged form: consecutive 64-lane tiles one workgroup walks through;
  *                         0 = chosen by group size: 4 above 32 rows, else 1 (default 0)
- *   "cache_resident_mib"  when a full-range call would move fewer MiB than this (default 192;
+ *   "cache_resident_mib"  when a full-range call would move fewer MiB than this (default 512;
  *                         the Infinity Cache holds 256 MiB) launches use plain accesses and no
  *                         residency cap, which is faster when nothing streams from HBM;
  *                         0 = always stream

@@ -18,7 +18,7 @@ std::atomic<int> g_nontemporal{2};         // se::Policy of the row accesses of 
 std::atomic<int> g_max_blocks_per_cu{-1}; // resident workgroups per CU (0 = no cap, -1 = chosen per launch)
 std::atomic<int> g_cooperative{0};        // LDS-staged form: 0 never, 1 always (and no split form then)
 std::atomic<int> g_coop_tiles{0};         // cooperative form: consecutive tiles per workgroup (0 = by group size)
-std::atomic<int> g_cache_resident_mib{192};  // launches moving fewer MiB stay in the 256 MiB Infinity Cache
+std::atomic<int> g_cache_resident_mib{512};  // calls moving fewer MiB per step run faster with plain accesses (256 MiB Infinity Cache)
 std::atomic<int> g_split{-1};             // split form for more than 8 rows per group: 0 never, 1 always, -1 where it measured faster
 std::atomic<int> g_split_scratch_mib{128}; // size of the split form's intermediate buffer
 std::atomic<int> g_split_sub_tiles{0};    // tiles per sub-chunk of the split form's finish launch (0 = by mode)
@@ -160,12 +160,12 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     // Split form: two launches per chunk of columns with an intermediate in a library-owned
     // buffer; for reductions over more than 8 rows on the 128-bit path.  Measured on MI355X it
     // beats the one-launch forms by 6-20 % for the gradient-averaging modes (the Ring-SGD
-    // baseline) and the SESGD update once a launch moves about a GiB, and it does not depend on
+    // baseline) and the SESGD update once a launch moves about 2 GiB, and it does not depend on
     // where the driver happened to place the buffers; the parameter average alone is faster in
     // one launch.
     const int split = g_split.load();
     const bool split_pays = j.mode != se::kAvgOnly &&
-                            (uint64_t)j.n * (uint64_t)(c1 - c0) * per_elem >= ((uint64_t)1 << 30);
+                            (uint64_t)j.n * (uint64_t)(c1 - c0) * per_elem >= ((uint64_t)1 << 31);
     if (vec == 4 && streams && j.m > (int)se::kSumBlockHost && coop <= 0 &&
         (split > 0 || (split < 0 && split_pays))) {
         const uint32_t nb = ((uint32_t)j.m + se::kSumBlockHost - 1u) / se::kSumBlockHost;
@@ -173,33 +173,36 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
         se::SplitShape sh;
         // Sub-chunks of 4096 tiles (4 MiB of every row) measured best when one mean gradient is
         // re-read per row, 256-2048 tiles alike and 4096 5 % slower when 8 block sums are.
-        sh.sub_tiles = (uint32_t)g_split_sub_tiles.load() / 8u * 8u;
-        if (sh.sub_tiles == 0) sh.sub_tiles = j.mode == se::kGradAvg ? 4096u : 2048u;
+        uint64_t sub_target = (uint64_t)g_split_sub_tiles.load() / 8u * 8u;
+        if (sub_target == 0) sub_target = j.mode == se::kGradAvg ? 4096u : 2048u;
+        // Chunks as large as the buffer allows, all of the same size, each cut into sub-chunks of
+        // the same size (a short last sub-chunk would switch rows every few tiles).
         const uint64_t budget = (uint64_t)g_split_scratch_mib.load() << 20;
-        uint64_t chunk = budget / ((uint64_t)slots * 1024u);            // 1 KiB per slot and tile
+        uint64_t max_chunk = budget / ((uint64_t)slots * 1024u);         // 1 KiB per slot and tile
+        if (max_chunk < 8u) max_chunk = 8u;
         const uint64_t all = ((uint64_t)a.tiles + 7u) / 8u * 8u;
-        if (chunk > all) chunk = all;
-        if (chunk < sh.sub_tiles) sh.sub_tiles = (uint32_t)(chunk / 8u * 8u);
-        if (sh.sub_tiles >= 8u) {
-            chunk = chunk / sh.sub_tiles * sh.sub_tiles;
-            sh.chunk_tiles = (uint32_t)chunk;
-            sh.scratch = se::split_scratch(j.stream, (size_t)(chunk * slots * 1024u));
-            if (sh.scratch) {
-                int fr = g_split_finish_rows.load();
-                if (j.mode == se::kGradAvg) fr = fr >= 4 ? 4 : fr >= 2 ? 2 : 1;
-                else fr = fr < 8 ? 8 : fr / 8 * 8;
-                sh.finish_rows = fr;
-                // Resident workgroups per CU, from sweeps on the ResNet-50, VGG-16 and BERT shapes:
-                // the mean-gradient pass has 8 KiB or less in flight per wavefront and wants 12 or
-                // more, the one-row update 24; the 8-row SESGD pass 4 (6 with bf16 gradients),
-                // the pass that writes the mean 16.
-                int cr = g_split_cap_reduce.load(), cf = g_split_cap_finish.load();
-                if (cr < 0) cr = j.mode == se::kGradAvg ? 12 : j.grad_bytes == 2 ? 6 : 4;
-                if (cf < 0) cf = j.mode == se::kGradAvg ? 24 : 16;
-                sh.lds_reduce = cr > 0 ? (se::kLdsPerCu / (uint32_t)cr) & ~1023u : 0u;
-                sh.lds_finish = cf > 0 ? (se::kLdsPerCu / (uint32_t)cf) & ~1023u : 0u;
-                return se::launch_split(a, s, sh, j.stream);
-            }
+        const uint64_t nchunks = (all + max_chunk - 1u) / max_chunk;
+        const uint64_t chunk_target = (all + nchunks - 1u) / nchunks;
+        const uint64_t nsub = (chunk_target + sub_target - 1u) / sub_target;
+        sh.sub_tiles = (uint32_t)(((chunk_target + nsub - 1u) / nsub + 7u) / 8u * 8u);
+        const uint64_t chunk = (uint64_t)sh.sub_tiles * nsub;
+        sh.chunk_tiles = (uint32_t)chunk;
+        sh.scratch = se::split_scratch(j.stream, (size_t)(chunk * slots * 1024u));
+        if (sh.scratch) {
+            int fr = g_split_finish_rows.load();
+            if (j.mode == se::kGradAvg) fr = fr >= 4 ? 4 : fr >= 2 ? 2 : 1;
+            else fr = fr < 8 ? 8 : fr / 8 * 8;
+            sh.finish_rows = fr;
+            // Resident workgroups per CU, from sweeps on the ResNet-50, VGG-16 and BERT shapes:
+            // the mean-gradient pass has 8 KiB or less in flight per wavefront and wants 12 or
+            // more, the one-row update 24; the 8-row SESGD pass 4 (6 with bf16 gradients),
+            // the pass that writes the mean 16.
+            int cr = g_split_cap_reduce.load(), cf = g_split_cap_finish.load();
+            if (cr < 0) cr = j.mode == se::kGradAvg ? 12 : j.grad_bytes == 2 ? 6 : 4;
+            if (cf < 0) cf = j.mode == se::kGradAvg ? 24 : 16;
+            sh.lds_reduce = cr > 0 ? (se::kLdsPerCu / (uint32_t)cr) & ~1023u : 0u;
+            sh.lds_finish = cf > 0 ? (se::kLdsPerCu / (uint32_t)cf) & ~1023u : 0u;
+            return se::launch_split(a, s, sh, j.stream);
         }
     }
     if (use_coop) return se::launch_coop(a, s, j.stream);
