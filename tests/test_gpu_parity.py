@@ -443,6 +443,41 @@ def test_split_form_for_large_groups(sub_tiles, always_streaming):
     case.check("split: layer ranges, no momentum")
 
 
+@pytest.mark.parametrize("form", ["one launch", "lds staged", "split"])
+def test_summation_order_examples_by_hand_on_the_gpu(form, golden_dir, always_streaming):
+    """The hand-evaluated sums of tests/golden/summation_order_examples.json (blocks of 8
+    members in ascending id, then the block sums first to last) through every kernel form and
+    every entry point that adds rows up: they tell the documented order from a left-to-right
+    sum, other block sizes and reversed orders without going through the oracle."""
+    se.se_set_tuning("cooperative", 1 if form == "lds staged" else 0)
+    se.se_set_tuning("split", 1 if form == "split" else 0)
+    with open(os.path.join(golden_dir, "summation_order_examples.json")) as f:
+        cases = json.load(f)["cases"]
+    ncols = 8                                             # 128-bit path; every column holds the example
+    for c in cases:
+        vals = np.asarray(c["values"], np.float32)
+        n = vals.size
+        mean = float(np.float32(c["sum"]) / np.float32(n))
+        offs = [0, ncols]
+        rows = torch.from_numpy(np.repeat(vals[:, None], ncols, axis=1).copy()).cuda()
+        ones = torch.ones(n, ncols, device="cuda")
+        zeros = torch.zeros(n, ncols, device="cuda")
+        x = rows.clone()
+        se.se_step(x, ones, None, offs, n, n, 0, 0.0, 0.0)                       # x-hat = x
+        assert (x == mean).all().item(), (form, c["name"], "se_step")
+        x = rows.clone()
+        se.se_global_average(x, offs, n)
+        assert (x == mean).all().item(), (form, c["name"], "se_global_average")
+        x = zeros.clone()
+        se.se_ring_step(x, rows, None, offs, n, -1.0, 0.0)                      # x = 0 + mean gradient
+        assert (x == mean).all().item(), (form, c["name"], "se_ring_step")
+        x = zeros.clone()
+        se.se_step_ex(x, rows, None, offs, n, n, 0, -1.0, 0.0, 0.0, GA)
+        assert (x == mean).all().item(), (form, c["name"], "se_step_ex, gradients averaged")
+        for wrong in c["other_orders"].values():
+            assert float(np.float32(wrong) / np.float32(n)) != mean
+
+
 def test_steps_captured_in_a_graph_replay_correctly():
     """Ten se_step launches (a different iteration and gradient buffer each) captured in one
     HIP graph; every replay must continue the trajectory exactly as eager launches do.  The
