@@ -12,6 +12,7 @@
 
 #include "../../paper_2007_00433_amd/csrc/se_common.hpp"
 #include "../../include/sesgd.h"
+#include "../../include/sesgd_tuning.h"
 
 namespace {
 
@@ -55,9 +56,22 @@ hipError_t record(const se::StepArgs &a, const se::LaunchShape &s, bool coop)
 namespace se {
 hipError_t launch_step(const StepArgs &a, const LaunchShape &s, hipStream_t) { return record(a, s, false); }
 hipError_t launch_coop(const StepArgs &a, const LaunchShape &s, hipStream_t) { return record(a, s, true); }
+static size_t g_scratch_bytes = 0;      // what the last split_scratch call asked for
+static int g_split_launches = 0;
 hipError_t launch_split(const StepArgs &a, const LaunchShape &s, const SplitShape &sh, hipStream_t)
 {
+    ++g_split_launches;
     EXPECT(s.vec == 4 && a.m > 8 && sh.scratch != nullptr);
+    // the buffer holds one 1 KiB piece per tile of a chunk and slot (group, or group and block of 8)
+    const size_t slots = a.mode == se::kGradAvg ? (size_t)a.k : (size_t)a.k * (size_t)((a.m + 7) / 8);
+    EXPECT(g_scratch_bytes == (size_t)sh.chunk_tiles * slots * 1024u);
+    EXPECT(g_scratch_bytes <= ((size_t)129 << 20) || sh.chunk_tiles == sh.sub_tiles);
+    EXPECT(a.mode == se::kGradAvg ? (sh.finish_rows == 1 || sh.finish_rows == 2 || sh.finish_rows == 4)
+                                  : (sh.finish_rows >= 8 && sh.finish_rows % 8 == 0));
+    // chunks of equal size cover all tiles; the finish launch's grid stays far below 2^31
+    const uint64_t nchunks = ((uint64_t)a.tiles + sh.chunk_tiles - 1) / sh.chunk_tiles;
+    EXPECT(nchunks * sh.chunk_tiles < (uint64_t)a.tiles + nchunks * 8u * (sh.chunk_tiles / sh.sub_tiles) + 8u);
+    EXPECT((uint64_t)sh.chunk_tiles * 64u < ((uint64_t)1 << 31));
     EXPECT(sh.sub_tiles >= 8 && sh.sub_tiles % 8 == 0 && sh.chunk_tiles >= sh.sub_tiles && sh.chunk_tiles % sh.sub_tiles == 0);
     EXPECT(sh.lds_reduce <= se::kLdsPerCu && sh.lds_finish <= se::kLdsPerCu);
     return record(a, s, false);
@@ -66,6 +80,7 @@ float *split_scratch(hipStream_t, size_t bytes)
 {
     static float dummy;
     EXPECT(bytes > 0 && bytes <= ((size_t)4096 << 20));
+    g_scratch_bytes = bytes;
     return &dummy;
 }
 hipError_t launch_plan(uint64_t, int64_t, int, int, int32_t *, int32_t *, hipStream_t) { return hipSuccess; }
@@ -121,6 +136,32 @@ int main()
                g_recs[from].tiles == (25557056u / 4 + 63) / 64);
         EXPECT(se_ring_step((float *)X, (const float *)G, (float *)V, offs, 1, 16, 0.1f, 0.9f, nullptr) == SE_OK);
         EXPECT(!g_recs.back().coop && g_recs.back().mode == se::kGradAvg && g_recs.back().m == 16 && g_recs.back().k == 1);
+    }
+    // large reductions take the split form by themselves from 2 GiB per call, and on request
+    // for any size that streams; every shape of it is checked in the launch_split stand-in
+    {
+        const int before = se::g_split_launches;
+        const uintptr_t X = (uintptr_t)1 << 40, G = (uintptr_t)2 << 40, V = (uintptr_t)3 << 40;   // 1 TiB apart
+        for (int64_t pitch : {(int64_t)25558016, (int64_t)109483008, (int64_t)138357760, (int64_t)4 * 8191 * 64, (int64_t)1024}) {
+            int64_t offs[3] = {0, pitch / 8 * 4 + 256, pitch};
+            for (int n : {16, 32, 64}) for (int m : {16, 32, 64}) {
+                if (m > n) continue;
+                for (int forced = 0; forced < 2; ++forced) for (int first = 0; first < 2; ++first) {
+                    EXPECT(se_set_tuning("split", forced ? 1 : -1) == SE_OK);
+                    EXPECT(se_set_tuning("cache_resident_mib", forced ? 0 : 512) == SE_OK);
+                    EXPECT(se_set_tuning("split_sub_tiles", forced && first ? 8 : 0) == SE_OK);
+                    EXPECT(se_set_tuning("split_scratch_mib", forced && !first ? 1 : 128) == SE_OK);
+                    const size_t from = g_recs.size();
+                    EXPECT(se_step_ex((float *)X, (const void *)G, m == 32, (float *)V, offs, 2, first, 2, n, m, 3, 0.1f, 0.9f, 0.0f,
+                                      (n == 32) ? SE_FLAG_GRAD_AVG : 0u, nullptr) == SE_OK);
+                    expect_exact_cover(from, X, offs[first], offs[2]);
+                    EXPECT(g_recs.size() == from + 1);            // one record per call: no head or tail pieces here
+                }
+            }
+        }
+        EXPECT(se::g_split_launches > before + 60);
+        se_set_tuning("split", -1); se_set_tuning("cache_resident_mib", 512);
+        se_set_tuning("split_sub_tiles", 0); se_set_tuning("split_scratch_mib", 128);
     }
     // error paths write nothing and launch nothing
     {
