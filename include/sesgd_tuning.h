@@ -21,10 +21,14 @@ int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
 /* Launch-shape knobs for measurement sweeps; results never depend on them (process-wide).
  *   "max_blocks_per_cu"   one-launch forms: cap on resident workgroups per compute unit, enforced
  *                         by requesting 160 KiB / cap of (unused) LDS per workgroup; 0 = no cap;
- *                         -1 (default) = the measured optimum per launch: 16, 12, 6 for group
- *                         sizes 1, 2, 4 (about 72 KiB of loads in flight per compute unit), 4 up
- *                         to 8 rows, 2 beyond, 2 for gradient averaging, 4 for the global
- *                         average, 8 for the LDS-staged form
+ *                         -1 (default) = the measured optimum per launch: 16, 12, 8 for group
+ *                         sizes 1, 2, 4 (11 for 4 with bf16 gradients), 5 up to 8 rows (6 with
+ *                         bf16 gradients), 2 beyond, 2 for gradient averaging, 4 for the global
+ *                         average, 8 for the LDS-staged form; none for calls below
+ *                         "cache_resident_mib"
+ *   "batch_rows"          single-wavefront SESGD update: member rows whose loads are issued back
+ *                         to back (1, 2, 4, 8); 0 (default) = 1 for groups up to 4, 2 up to 8, 8
+ *                         beyond; all rows of a small group at once below "cache_resident_mib"
  *   "nontemporal"         cache policy of the row accesses: 0 plain; 1 streaming (non-temporal)
  *                         loads and stores; 2 (default) streaming, and stores written through
  *                         the L2 to memory at once (measured 2-4 % faster than 1)

@@ -24,6 +24,7 @@ std::atomic<int> g_split_scratch_mib{128}; // size of the split form's intermedi
 std::atomic<int> g_split_sub_tiles{0};    // tiles per sub-chunk of the split form's finish launch (0 = by mode)
 std::atomic<int> g_split_cap_reduce{-1};  // resident workgroups per CU of the two launches (0 = no cap, -1 = default)
 std::atomic<int> g_split_cap_finish{-1};
+std::atomic<int> g_batch_rows{0};         // single-wavefront SESGD update: rows per batch of loads (0 = by group size)
 std::atomic<int> g_split_finish_rows{0};  // rows per wavefront of the finish launch (0 = default)
 
 thread_local char t_last_error[256] = "";
@@ -80,22 +81,35 @@ struct Job {
     hipStream_t stream;
 };
 
-// Resident single-wavefront workgroups per CU, from sweeps on MI355X (fp32 and bf16 gradients,
-// n = 16, 32, 64).  Up to 4 rows per group all loads of a tile are issued at once and about
-// 72 KiB in flight per CU is the optimum: 6 workgroups for the headline shape (4 members x 3
-// arrays x 1 KiB per wavefront), 12 for groups of 2, 16 for group_size 1.  Larger groups are
-// walked in batches of 8 rows: 4 workgroups up to 8 rows, 2 beyond; gradient averaging (the
-// ring) 2; parameter averaging 4.
-// Fewer starve the memory system, more scatter the tiles in flight and lose DRAM locality.
-int auto_blocks_per_cu(const Job &j, int vec)
+// Rows a wavefront of the single-wavefront SESGD update loads back to back, and resident
+// workgroups per CU, from sweeps on MI355X (ResNet-50, VGG-16 and BERT shapes; fp32 and bf16
+// gradients; n = 16, 32, 64).  One row at a time (x, g, v of one member, then the next) with 8
+// workgroups per CU measured 1-3 % faster for groups of 4 than all 4 rows at once with 6; groups
+// of 5 to 8 run best two rows at a time.  Fewer workgroups starve the memory system, more
+// scatter the tiles in flight; rows of bf16 gradients are shorter and want a few more.
+int auto_batch_rows(const Job &j, bool streams, uint64_t launch_bytes)
+{
+    if (j.mode != se::kSesgd) return 8;
+    // Buffers small enough for plain accesses: all rows of a small group at once is 0-5 % faster.
+    // Launches over few columns (a layer range) are over before the order of the rows matters;
+    // there one round trip for all rows is what counts (161 per-tensor launches of the
+    // ResNet-50 shape: 566 against 530 steps/s).
+    if (!streams || launch_bytes < ((uint64_t)64 << 20)) return j.m >= 8 ? 8 : 4;
+    return j.m <= 4 ? 1 : j.m <= 8 ? 2 : 8;
+}
+
+int auto_blocks_per_cu(const Job &j, int batch)
 {
     if (j.mode == se::kGradAvg) return 2;
     if (j.mode == se::kAvgOnly) return 4;
     if (j.m > 8) return 2;
-    if (j.m > 4) return 4;
-    const int in_flight = j.m * 64 * vec * (4 + j.grad_bytes + (j.v ? 4 : 0));   // bytes per wavefront
-    const int cap = 72 * 1024 / in_flight;
-    return cap < 4 ? 4 : cap > 16 ? 16 : cap;
+    const bool bf16 = j.grad_bytes == 2;
+    if (batch >= 8) return 4;
+    if (batch >= 4) return 6;
+    if (j.m == 1) return 16;
+    if (j.m == 2) return 12;
+    if (j.m <= 4) return bf16 ? 11 : 8;
+    return bf16 ? 6 : 5;                      // 5 to 8 rows, two at a time
 }
 
 // One launch over columns [c0, c1) with `vec` columns per lane; (c1 - c0) % vec == 0 and every
@@ -149,13 +163,16 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     const uint64_t moved = (uint64_t)j.n * (uint64_t)j.pitch * per_elem;
     const bool streams = moved >= ((uint64_t)g_cache_resident_mib.load() << 20);
     s.policy = streams ? g_nontemporal.load() : se::kPlain;
+    s.batch_rows = g_batch_rows.load();
+    if (s.batch_rows <= 0)
+        s.batch_rows = auto_batch_rows(j, streams, (uint64_t)j.n * (uint64_t)(c1 - c0) * per_elem);
     // The LDS-staged form (one block of 8 rows per wavefront, block sums staged in LDS) measured
     // slower than the single-wavefront form for every group size (0.5-7 %) and than the split
     // form for large ones; it runs only when asked for.
     const int coop = g_cooperative.load();
     const bool use_coop = coop > 0;
     int cap = g_max_blocks_per_cu.load();
-    if (cap < 0) cap = !streams ? 0 : use_coop ? 8 : auto_blocks_per_cu(j, vec);
+    if (cap < 0) cap = !streams ? 0 : use_coop ? 8 : auto_blocks_per_cu(j, s.batch_rows);
     s.lds_bytes = cap > 0 ? (se::kLdsPerCu / (uint32_t)cap) & ~1023u : 0u;
     // Split form: two launches per chunk of columns with an intermediate in a library-owned
     // buffer; for reductions over more than 8 rows on the 128-bit path.  Measured on MI355X it
@@ -272,6 +289,7 @@ Knob kKnobs[] = {
     {"split_cap_reduce", &g_split_cap_reduce, -1, 32},
     {"split_cap_finish", &g_split_cap_finish, -1, 32},
     {"split_finish_rows", &g_split_finish_rows, 0, 64},
+    {"batch_rows", &g_batch_rows, 0, 8},
 };
 
 }  // namespace

@@ -45,6 +45,7 @@ struct LaunchShape {
     bool bf16;              // gradient storage
     int policy;             // Policy of the row accesses
     uint32_t lds_bytes;     // dynamic LDS requested only to cap resident workgroups per CU
+    int batch_rows;         // single-wavefront SESGD update: rows per batch of loads (0 = by group size)
 };
 
 // Split form: what the host decides per call.

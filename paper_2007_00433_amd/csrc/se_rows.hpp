@@ -110,30 +110,29 @@ __device__ __forceinline__ void update_batch(const StepArgs &p, uint64_t &todo, 
 // The library's summation order: the m members (ascending worker id) are cut into consecutive
 // blocks of kSumBlock = 8, each block is added up left to right, then the block sums are added
 // up left to right.  CALL(B, FIRST, acc) must add B members to acc, left to right, starting acc
-// afresh when FIRST.  A full block is one batch of 8 (BMAX == 8) or two of 4; a shorter last
-// block is walked in batches of 4, 2, 1.  The total lands in `total`.
+// afresh when FIRST.  A block is walked in batches of at most BMAX rows: 8, then 4, 2, 1.  The total lands in `total`.
 constexpr int kSumBlock = 8;
 #define SE_SUM_MEMBER_BLOCKS(BMAX, m, VEC_, total, CALL)                                   \
     do {                                                                                   \
-        static_assert(BMAX == 8 || BMAX == 4, "batch size");                               \
+        static_assert(BMAX == 8 || BMAX == 4 || BMAX == 2 || BMAX == 1, "batch size");     \
         int rem_ = (m);                                                                    \
         bool first_block_ = true;                                                          \
         while (rem_ > 0) {                                                                 \
             Pack<VEC_> part_;                                                              \
-            if (rem_ >= kSumBlock) {                                                       \
-                if constexpr (BMAX == 8) { CALL(8, true, part_); }                         \
-                else { CALL(4, true, part_); CALL(4, false, part_); }                      \
-                rem_ -= kSumBlock;                                                         \
-            } else {                                                                       \
-                bool first_ = true;                                                        \
-                if (rem_ >= 4) { CALL(4, true, part_); rem_ -= 4; first_ = false; }        \
-                if (rem_ >= 2) {                                                           \
-                    if (first_) { CALL(2, true, part_); } else { CALL(2, false, part_); }  \
-                    rem_ -= 2; first_ = false; }                                           \
-                if (rem_ >= 1) {                                                           \
-                    if (first_) { CALL(1, true, part_); } else { CALL(1, false, part_); }  \
-                    rem_ -= 1; }                                                           \
-            }                                                                              \
+            int blk_ = rem_ < kSumBlock ? rem_ : kSumBlock;                                \
+            rem_ -= blk_;                                                                  \
+            bool first_ = true;                                                            \
+            if constexpr (BMAX >= 8) { if (blk_ == 8) {                                    \
+                CALL(8, true, part_); blk_ = 0; first_ = false; } }                        \
+            if constexpr (BMAX >= 4) { while (blk_ >= 4) {                                 \
+                if (first_) { CALL(4, true, part_); } else { CALL(4, false, part_); }      \
+                blk_ -= 4; first_ = false; } }                                             \
+            if constexpr (BMAX >= 2) { while (blk_ >= 2) {                                 \
+                if (first_) { CALL(2, true, part_); } else { CALL(2, false, part_); }      \
+                blk_ -= 2; first_ = false; } }                                             \
+            while (blk_ >= 1) {                                                            \
+                if (first_) { CALL(1, true, part_); } else { CALL(1, false, part_); }      \
+                blk_ -= 1; first_ = false; }                                               \
             _Pragma("unroll")                                                              \
             for (int q_ = 0; q_ < VEC_; ++q_)                                              \
                 total.a[q_] = first_block_ ? part_.a[q_] : total.a[q_] + part_.a[q_];      \

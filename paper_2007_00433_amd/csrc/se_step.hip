@@ -101,10 +101,14 @@ template <int VEC, bool BF16, int NT>
 static hipError_t launch_mode(const StepArgs &a, const LaunchShape &s, hipStream_t stream)
 {
     switch (a.mode) {
-    case kSesgd:
-        // deeper batches keep more rows in flight for large groups
-        return a.m >= 8 ? launch_flags<VEC, BF16, NT, kSesgd, 8>(a, s, stream)
-                        : launch_flags<VEC, BF16, NT, kSesgd, 4>(a, s, stream);
+    case kSesgd: {
+        // rows loaded back to back per batch (chosen by the caller from the group size)
+        const int batch = s.batch_rows > 0 ? s.batch_rows : 8;
+        if (batch >= 8) return launch_flags<VEC, BF16, NT, kSesgd, 8>(a, s, stream);
+        if (batch >= 4) return launch_flags<VEC, BF16, NT, kSesgd, 4>(a, s, stream);
+        if (batch >= 2) return launch_flags<VEC, BF16, NT, kSesgd, 2>(a, s, stream);
+        return launch_flags<VEC, BF16, NT, kSesgd, 1>(a, s, stream);
+    }
     case kGradAvg:
         return launch_flags<VEC, BF16, NT, kGradAvg, 8>(a, s, stream);
     default:

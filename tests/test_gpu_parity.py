@@ -355,7 +355,9 @@ def test_results_do_not_depend_on_launch_knobs_or_stream():
               dict(cooperative=1, coop_tiles=1), dict(cooperative=1, coop_tiles=7),
               dict(cooperative=1, coop_tiles=4096),
               dict(cache_resident_mib=0, split=1), dict(cache_resident_mib=0, split=1, split_scratch_mib=1, split_sub_tiles=8),
-              dict(cache_resident_mib=0, split=1, split_cap_reduce=0, split_cap_finish=2)]
+              dict(cache_resident_mib=0, split=1, split_cap_reduce=0, split_cap_finish=2),
+              dict(batch_rows=1), dict(batch_rows=2, cache_resident_mib=0), dict(batch_rows=4, cache_resident_mib=0),
+              dict(batch_rows=8), dict(batch_rows=1, cache_resident_mib=0, max_blocks_per_cu=3)]
     defaults = {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}
     for q, shape in enumerate(shapes):
         for k, val in {**defaults, **shape}.items():
@@ -898,7 +900,7 @@ def test_randomised_configurations():
                      coop_tiles=int(rng.choice([1, 2, 4, 5, 64])),
                      max_blocks_per_cu=int(rng.choice([-1, 0, 1, 6, 32])), cache_resident_mib=int(rng.choice([0, 192])),
                      split=int(rng.choice([-1, 0, 1])), split_sub_tiles=int(rng.choice([8, 512])),
-                     split_scratch_mib=int(rng.choice([1, 64])))
+                     split_scratch_mib=int(rng.choice([1, 64])), batch_rows=int(rng.choice([0, 1, 2, 4, 8])))
         for k, val in {**defaults, **knobs}.items():
             se.se_set_tuning(k, val)
         se.se_set_seed(int(rng.integers(0, 2 ** 63)))
