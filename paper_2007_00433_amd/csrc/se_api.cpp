@@ -183,9 +183,9 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     const int split = g_split.load();
     const bool split_pays = j.mode != se::kAvgOnly &&
                             (uint64_t)j.n * (uint64_t)(c1 - c0) * per_elem >= ((uint64_t)1 << 31);
-    if (vec == 4 && streams && j.m > (int)se::kSumBlockHost && coop <= 0 &&
+    if (vec == 4 && streams && j.m > se::kSumBlock && coop <= 0 &&
         (split > 0 || (split < 0 && split_pays))) {
-        const uint32_t nb = ((uint32_t)j.m + se::kSumBlockHost - 1u) / se::kSumBlockHost;
+        const uint32_t nb = (uint32_t)((j.m + se::kSumBlock - 1) / se::kSumBlock);
         const uint32_t slots = j.mode == se::kGradAvg ? (uint32_t)a.k : (uint32_t)a.k * nb;
         se::SplitShape sh;
         // Sub-chunks of 4096 tiles (4 MiB of every row) measured best when one mean gradient is

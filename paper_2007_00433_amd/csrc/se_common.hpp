@@ -11,7 +11,7 @@ namespace se {
 
 constexpr int kMaxWorkers = 64;              // one lane per worker in the plan generator
 constexpr uint32_t kLdsPerCu = 160 * 1024;   // gfx950 LDS per compute unit
-constexpr uint32_t kSumBlockHost = 8;        // members per block of the summation order
+constexpr int kSumBlock = 8;                 // members per block of the library's summation order
 
 // What a step kernel computes per group (see se_step.hip for the passages).
 enum Mode : int { kSesgd = 0, kGradAvg = 1, kAvgOnly = 2 };

@@ -19,7 +19,7 @@
 
 namespace se {
 
-constexpr int kRowsPerWave = 8;      // = the block length of the summation order
+constexpr int kRowsPerWave = kSumBlock;   // one block of the summation order per wavefront
 
 template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, int NT, int MODE>
 __global__ __launch_bounds__(64 * ((kMaxWorkers + kRowsPerWave - 1) / kRowsPerWave))

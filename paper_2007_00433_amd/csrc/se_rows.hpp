@@ -111,7 +111,6 @@ __device__ __forceinline__ void update_batch(const StepArgs &p, uint64_t &todo, 
 // blocks of kSumBlock = 8, each block is added up left to right, then the block sums are added
 // up left to right.  CALL(B, FIRST, acc) must add B members to acc, left to right, starting acc
 // afresh when FIRST.  A block is walked in batches of at most BMAX rows: 8, then 4, 2, 1.  The total lands in `total`.
-constexpr int kSumBlock = 8;
 #define SE_SUM_MEMBER_BLOCKS(BMAX, m, VEC_, total, CALL)                                   \
     do {                                                                                   \
         static_assert(BMAX == 8 || BMAX == 4 || BMAX == 2 || BMAX == 1, "batch size");     \

@@ -41,7 +41,7 @@ struct SplitArgs {
     int finish_units;        // wavefronts per group and tile of the finish launch
 };
 
-constexpr int VEC = 4;       // the split form exists for the 128-bit path only
+constexpr int kVec = 4;      // the split form exists for the 128-bit path only
 
 // members of `mask` from number `skip` on (ascending worker id)
 __device__ __forceinline__ uint64_t skip_members(uint64_t mask, int skip)
@@ -63,35 +63,35 @@ __global__ __launch_bounds__(64) void se_split_reduce_kernel(const SplitArgs q)
 
     const uint32_t c = (q.tile0 + blockIdx.x) * 64u + threadIdx.x;
     if (c < p.lead || c >= p.nvec) return;
-    const uint32_t off = c * (uint32_t)(VEC * 4);
+    const uint32_t off = c * (uint32_t)(kVec * 4);
     const uint32_t goff = BF16 ? off / 2 : off;
 
-    Pack<VEC> s;
+    Pack<kVec> s;
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) s.a[i] = 0.0f;
+    for (int i = 0; i < kVec; ++i) s.a[i] = 0.0f;
     if constexpr (MODE == kGradAvg) {
         uint64_t todo = members;
-#define SE_CALL(B, F, ACC) sum_batch<VEC, BF16, NT, false, B, F>(p, todo, goff, gpitch_bytes, ACC)
-        SE_SUM_MEMBER_BLOCKS(8, p.m, VEC, s, SE_CALL);
+#define SE_CALL(B, F, ACC) sum_batch<kVec, BF16, NT, false, B, F>(p, todo, goff, gpitch_bytes, ACC)
+        SE_SUM_MEMBER_BLOCKS(8, p.m, kVec, s, SE_CALL);
 #undef SE_CALL
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) s.a[i] = s.a[i] * p.inv_m;
+        for (int i = 0; i < kVec; ++i) s.a[i] = s.a[i] * p.inv_m;
     } else {
         uint64_t todo = skip_members(members, b * kSumBlock);
         const int count = min(kSumBlock, p.m - b * kSumBlock);           // one block: a single partial
         if constexpr (MODE == kSesgd) {
-#define SE_CALL(B, F, ACC) sesgd_batch<VEC, BF16, HAS_V, HAS_WD, NT, B, F>(p, todo, off, goff, gpitch_bytes, ACC)
-            SE_SUM_MEMBER_BLOCKS(8, count, VEC, s, SE_CALL);
+#define SE_CALL(B, F, ACC) sesgd_batch<kVec, BF16, HAS_V, HAS_WD, NT, B, F>(p, todo, off, goff, gpitch_bytes, ACC)
+            SE_SUM_MEMBER_BLOCKS(8, count, kVec, s, SE_CALL);
 #undef SE_CALL
         } else {
-#define SE_CALL(B, F, ACC) sum_batch<VEC, false, NT, true, B, F>(p, todo, off, p.pitch_bytes, ACC)
-            SE_SUM_MEMBER_BLOCKS(8, count, VEC, s, SE_CALL);
+#define SE_CALL(B, F, ACC) sum_batch<kVec, false, NT, true, B, F>(p, todo, off, p.pitch_bytes, ACC)
+            SE_SUM_MEMBER_BLOCKS(8, count, kVec, s, SE_CALL);
 #undef SE_CALL
         }
     }
     // plain store: the value is wanted again soon, from cache
-    float *dst = q.scratch + (size_t)slot * q.chunk_pitch + ((size_t)blockIdx.x * 64u + threadIdx.x) * VEC;
-    store_f32<VEC, kPlain>((char *)dst, 0u, s);
+    float *dst = q.scratch + (size_t)slot * q.chunk_pitch + ((size_t)blockIdx.x * 64u + threadIdx.x) * kVec;
+    store_f32<kVec, kPlain>((char *)dst, 0u, s);
 }
 
 template <bool HAS_V, bool HAS_WD, int NT, int MODE>
@@ -114,28 +114,28 @@ __global__ __launch_bounds__(64) void se_split_finish_kernel(const SplitArgs q)
     const uint64_t members = wave_members(p.seed, p.iter, p.n, p.m, g, lane);
     const uint32_t c = (q.tile0 + t) * 64u + threadIdx.x;
     if (c < p.lead || c >= p.nvec) return;
-    const uint32_t off = c * (uint32_t)(VEC * 4);
-    const size_t scol = ((size_t)t * 64u + threadIdx.x) * VEC;
+    const uint32_t off = c * (uint32_t)(kVec * 4);
+    const size_t scol = ((size_t)t * 64u + threadIdx.x) * kVec;
     uint64_t todo = skip_members(members, r0);
 
     if constexpr (MODE == kGradAvg) {
-        const Pack<VEC> gbar = load_f32<VEC, kPlain>((const char *)(q.scratch + (size_t)g * q.chunk_pitch + scol));
-#define SE_CALL(B, F) update_batch<VEC, HAS_V, HAS_WD, NT, B, F>(p, todo, off, gbar)
+        const Pack<kVec> gbar = load_f32<kVec, kPlain>((const char *)(q.scratch + (size_t)g * q.chunk_pitch + scol));
+#define SE_CALL(B, F) update_batch<kVec, HAS_V, HAS_WD, NT, B, F>(p, todo, off, gbar)
         SE_FOR_MEMBER_BATCHES(4, count, SE_CALL);
 #undef SE_CALL
     } else {
         const float *part = q.scratch + (size_t)g * q.nb * q.chunk_pitch + scol;
-        Pack<VEC> s = load_f32<VEC, kPlain>((const char *)part);
+        Pack<kVec> s = load_f32<kVec, kPlain>((const char *)part);
         for (int bb = 1; bb < q.nb; ++bb) {
-            const Pack<VEC> u = load_f32<VEC, kPlain>((const char *)(part + (size_t)bb * q.chunk_pitch));
+            const Pack<kVec> u = load_f32<kVec, kPlain>((const char *)(part + (size_t)bb * q.chunk_pitch));
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) s.a[i] = s.a[i] + u.a[i];
+            for (int i = 0; i < kVec; ++i) s.a[i] = s.a[i] + u.a[i];
         }
-        Pack<VEC> mean;
+        Pack<kVec> mean;
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) mean.a[i] = s.a[i] * p.inv_m;
+        for (int i = 0; i < kVec; ++i) mean.a[i] = s.a[i] * p.inv_m;
         for (int i = 0; i < count; ++i)
-            store_f32<VEC, NT>((char *)p.x + next_row(todo) * p.pitch_bytes, off, mean);
+            store_f32<kVec, NT>((char *)p.x + next_row(todo) * p.pitch_bytes, off, mean);
     }
 }
 
@@ -211,7 +211,7 @@ static hipError_t launch_chunks(const StepArgs &a, const SplitShape &sh, hipStre
     q.finish_rows = sh.finish_rows;
     q.finish_units = (a.m + sh.finish_rows - 1) / sh.finish_rows;
     const uint32_t units = (uint32_t)(a.k * q.finish_units);
-    q.chunk_pitch = sh.chunk_tiles * 64u * VEC;
+    q.chunk_pitch = sh.chunk_tiles * 64u * kVec;
     for (uint32_t tile0 = 0; tile0 < a.tiles; tile0 += sh.chunk_tiles) {
         q.tile0 = tile0;
         q.tiles_c = a.tiles - tile0 < sh.chunk_tiles ? a.tiles - tile0 : sh.chunk_tiles;
@@ -250,7 +250,7 @@ static hipError_t launch_mode(const StepArgs &a, const SplitShape &sh, hipStream
 
 hipError_t launch_split(const StepArgs &a, const LaunchShape &s, const SplitShape &sh, hipStream_t stream)
 {
-    if (s.vec != VEC || !sh.scratch || sh.chunk_tiles == 0 || sh.sub_tiles == 0) return hipErrorInvalidValue;
+    if (s.vec != kVec || !sh.scratch || sh.chunk_tiles == 0 || sh.sub_tiles == 0) return hipErrorInvalidValue;
     const int fr = sh.finish_rows;
     if (a.mode == kGradAvg ? (fr != 1 && fr != 2 && fr != 4) : (fr < kSumBlock || fr % kSumBlock != 0))
         return hipErrorInvalidValue;
