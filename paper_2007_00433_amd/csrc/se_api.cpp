@@ -186,12 +186,12 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     if (vec == 4 && streams && j.m > se::kSumBlock && coop <= 0 &&
         (split > 0 || (split < 0 && split_pays))) {
         const uint32_t nb = (uint32_t)((j.m + se::kSumBlock - 1) / se::kSumBlock);
-        const uint32_t slots = j.mode == se::kGradAvg ? (uint32_t)a.k : (uint32_t)a.k * nb;
+        const uint32_t slots = j.mode == se::kSesgd ? (uint32_t)a.k * nb : (uint32_t)a.k;
         se::SplitShape sh;
         // Sub-chunks of 4096 tiles (4 MiB of every row) measured best when one mean gradient is
         // re-read per row, 256-2048 tiles alike and 4096 5 % slower when 8 block sums are.
         uint64_t sub_target = (uint64_t)g_split_sub_tiles.load() / 8u * 8u;
-        if (sub_target == 0) sub_target = j.mode == se::kGradAvg ? 4096u : 2048u;
+        if (sub_target == 0) sub_target = j.mode == se::kSesgd ? 2048u : 4096u;
         // Chunks as large as the buffer allows, all of the same size, each cut into sub-chunks of
         // the same size (a short last sub-chunk would switch rows every few tiles).
         const uint64_t budget = (uint64_t)g_split_scratch_mib.load() << 20;
@@ -208,6 +208,7 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
         if (sh.scratch) {
             int fr = g_split_finish_rows.load();
             if (j.mode == se::kGradAvg) fr = fr >= 4 ? 4 : fr >= 2 ? 2 : 1;
+            else if (j.mode == se::kAvgOnly) fr = fr < 1 ? 1 : fr;
             else fr = fr < 8 ? 8 : fr / 8 * 8;
             sh.finish_rows = fr;
             // Resident workgroups per CU, from sweeps on the ResNet-50, VGG-16 and BERT shapes:
@@ -215,8 +216,8 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
             // more, the one-row update 24; the 8-row SESGD pass 4 (6 with bf16 gradients),
             // the pass that writes the mean 16.
             int cr = g_split_cap_reduce.load(), cf = g_split_cap_finish.load();
-            if (cr < 0) cr = j.mode == se::kGradAvg ? 12 : j.grad_bytes == 2 ? 6 : 4;
-            if (cf < 0) cf = j.mode == se::kGradAvg ? 24 : 16;
+            if (cr < 0) cr = j.mode != se::kSesgd ? 12 : j.grad_bytes == 2 ? 6 : 4;
+            if (cf < 0) cf = j.mode != se::kSesgd ? 24 : 16;
             sh.lds_reduce = cr > 0 ? (se::kLdsPerCu / (uint32_t)cr) & ~1023u : 0u;
             sh.lds_finish = cf > 0 ? (se::kLdsPerCu / (uint32_t)cf) & ~1023u : 0u;
             return se::launch_split(a, s, sh, j.stream);

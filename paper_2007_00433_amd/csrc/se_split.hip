@@ -9,13 +9,16 @@
 //            one wavefront per (tile, group) adds the group's gradients up -- blocks of 8
 //            members left to right, then the block sums left to right, the library's order --
 //            and stores the mean gradient.
-//            kSesgd (Sec. 3.2, the SESGD update equation) / kAvgOnly (Algorithm 1, last line):
-//            one wavefront per (tile, group, block of 8 members) does the local momentum/SGD
-//            step of its 8 rows (kSesgd), stores v, and stores the block's sum of x-hat (or x).
+//            kAvgOnly (Algorithm 1, last line): the same over the group's parameters; the mean
+//            parameters are stored.
+//            kSesgd (Sec. 3.2, the SESGD update equation): one wavefront per (tile, group, block
+//            of 8 members) does the local momentum/SGD step of its 8 rows, stores v, and stores
+//            the block's sum of x-hat.
 //   finish   kGradAvg: one wavefront per (tile, worker) updates that worker's v and x with the
-//            stored mean gradient.
-//            kSesgd / kAvgOnly: one wavefront per (tile, group, block) adds the group's stored
-//            block sums left to right, scales by 1/m and writes the mean to its 8 rows.
+//            stored mean gradient.  kAvgOnly: one wavefront per (tile, worker) writes the stored
+//            mean into that worker's row.
+//            kSesgd: one wavefront per (tile, group, block) adds the group's stored block sums
+//            left to right, scales by 1/m and writes the mean to its 8 rows.
 //
 // The finish launch walks its work in sub-chunks of `sub_tiles` tiles: all tiles of a sub-chunk
 // for one worker (or block), then the same tiles for the next, so that the intermediate of a
@@ -30,7 +33,7 @@ namespace se {
 
 struct SplitArgs {
     StepArgs a;
-    float *scratch;          // [slots][chunk_pitch] fp32; slot = group (kGradAvg) or group * nb + block
+    float *scratch;          // [slots][chunk_pitch] fp32; slot = group, or group * nb + block in kSesgd
     uint32_t tile0;          // first tile of this chunk (tiles are counted as in `a`)
     uint32_t tiles_c;        // tiles of this chunk
     uint32_t sub_tiles;      // tiles per sub-chunk of the finish launch
@@ -57,8 +60,9 @@ __global__ __launch_bounds__(64) void se_split_reduce_kernel(const SplitArgs q)
     const int lane = (int)threadIdx.x;
     const uint64_t gpitch_bytes = BF16 ? p.pitch_bytes / 2 : p.pitch_bytes;
     const uint32_t slot = blockIdx.y;
-    const uint32_t g = MODE == kGradAvg ? slot : slot / (uint32_t)q.nb;
-    const int b = MODE == kGradAvg ? 0 : (int)(slot - g * (uint32_t)q.nb);
+    constexpr bool kWholeGroup = MODE != kSesgd;          // one wavefront adds the whole group up
+    const uint32_t g = kWholeGroup ? slot : slot / (uint32_t)q.nb;
+    const int b = kWholeGroup ? 0 : (int)(slot - g * (uint32_t)q.nb);
     const uint64_t members = wave_members(p.seed, p.iter, p.n, p.m, g, lane);
 
     const uint32_t c = (q.tile0 + blockIdx.x) * 64u + threadIdx.x;
@@ -76,18 +80,19 @@ __global__ __launch_bounds__(64) void se_split_reduce_kernel(const SplitArgs q)
 #undef SE_CALL
 #pragma unroll
         for (int i = 0; i < kVec; ++i) s.a[i] = s.a[i] * p.inv_m;
+    } else if constexpr (MODE == kAvgOnly) {
+        uint64_t todo = members;
+#define SE_CALL(B, F, ACC) sum_batch<kVec, false, NT, true, B, F>(p, todo, off, p.pitch_bytes, ACC)
+        SE_SUM_MEMBER_BLOCKS(8, p.m, kVec, s, SE_CALL);
+#undef SE_CALL
+#pragma unroll
+        for (int i = 0; i < kVec; ++i) s.a[i] = s.a[i] * p.inv_m;
     } else {
         uint64_t todo = skip_members(members, b * kSumBlock);
         const int count = min(kSumBlock, p.m - b * kSumBlock);           // one block: a single partial
-        if constexpr (MODE == kSesgd) {
 #define SE_CALL(B, F, ACC) sesgd_batch<kVec, BF16, HAS_V, HAS_WD, NT, B, F>(p, todo, off, goff, gpitch_bytes, ACC)
-            SE_SUM_MEMBER_BLOCKS(8, count, kVec, s, SE_CALL);
+        SE_SUM_MEMBER_BLOCKS(8, count, kVec, s, SE_CALL);
 #undef SE_CALL
-        } else {
-#define SE_CALL(B, F, ACC) sum_batch<kVec, false, NT, true, B, F>(p, todo, off, p.pitch_bytes, ACC)
-            SE_SUM_MEMBER_BLOCKS(8, count, kVec, s, SE_CALL);
-#undef SE_CALL
-        }
     }
     // plain store: the value is wanted again soon, from cache
     float *dst = q.scratch + (size_t)slot * q.chunk_pitch + ((size_t)blockIdx.x * 64u + threadIdx.x) * kVec;
@@ -123,6 +128,10 @@ __global__ __launch_bounds__(64) void se_split_finish_kernel(const SplitArgs q)
 #define SE_CALL(B, F) update_batch<kVec, HAS_V, HAS_WD, NT, B, F>(p, todo, off, gbar)
         SE_FOR_MEMBER_BATCHES(4, count, SE_CALL);
 #undef SE_CALL
+    } else if constexpr (MODE == kAvgOnly) {
+        const Pack<kVec> mean = load_f32<kVec, kPlain>((const char *)(q.scratch + (size_t)g * q.chunk_pitch + scol));
+        for (int i = 0; i < count; ++i)
+            store_f32<kVec, NT>((char *)p.x + next_row(todo) * p.pitch_bytes, off, mean);
     } else {
         const float *part = q.scratch + (size_t)g * q.nb * q.chunk_pitch + scol;
         Pack<kVec> s = load_f32<kVec, kPlain>((const char *)part);
@@ -207,7 +216,7 @@ static hipError_t launch_chunks(const StepArgs &a, const SplitShape &sh, hipStre
     q.scratch = sh.scratch;
     q.nb = (a.m + kSumBlock - 1) / kSumBlock;
     q.sub_tiles = sh.sub_tiles;
-    const uint32_t slots = MODE == kGradAvg ? (uint32_t)a.k : (uint32_t)(a.k * q.nb);
+    const uint32_t slots = MODE == kSesgd ? (uint32_t)(a.k * q.nb) : (uint32_t)a.k;
     q.finish_rows = sh.finish_rows;
     q.finish_units = (a.m + sh.finish_rows - 1) / sh.finish_rows;
     const uint32_t units = (uint32_t)(a.k * q.finish_units);
@@ -252,7 +261,7 @@ hipError_t launch_split(const StepArgs &a, const LaunchShape &s, const SplitShap
 {
     if (s.vec != kVec || !sh.scratch || sh.chunk_tiles == 0 || sh.sub_tiles == 0) return hipErrorInvalidValue;
     const int fr = sh.finish_rows;
-    if (a.mode == kGradAvg ? (fr != 1 && fr != 2 && fr != 4) : (fr < kSumBlock || fr % kSumBlock != 0))
+    if (a.mode == kSesgd ? (fr < kSumBlock || fr % kSumBlock != 0) : a.mode == kGradAvg ? (fr != 1 && fr != 2 && fr != 4) : (fr < 1 || fr > kMaxWorkers))
         return hipErrorInvalidValue;
     if (s.bf16) {
         switch (s.policy) {

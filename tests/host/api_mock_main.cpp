@@ -63,11 +63,12 @@ hipError_t launch_split(const StepArgs &a, const LaunchShape &s, const SplitShap
     ++g_split_launches;
     EXPECT(s.vec == 4 && a.m > 8 && sh.scratch != nullptr);
     // the buffer holds one 1 KiB piece per tile of a chunk and slot (group, or group and block of 8)
-    const size_t slots = a.mode == se::kGradAvg ? (size_t)a.k : (size_t)a.k * (size_t)((a.m + 7) / 8);
+    const size_t slots = a.mode == se::kSesgd ? (size_t)a.k * (size_t)((a.m + 7) / 8) : (size_t)a.k;
     EXPECT(g_scratch_bytes == (size_t)sh.chunk_tiles * slots * 1024u);
     EXPECT(g_scratch_bytes <= ((size_t)129 << 20) || sh.chunk_tiles == sh.sub_tiles);
-    EXPECT(a.mode == se::kGradAvg ? (sh.finish_rows == 1 || sh.finish_rows == 2 || sh.finish_rows == 4)
-                                  : (sh.finish_rows >= 8 && sh.finish_rows % 8 == 0));
+    EXPECT(a.mode == se::kSesgd ? (sh.finish_rows >= 8 && sh.finish_rows % 8 == 0)
+           : a.mode == se::kGradAvg ? (sh.finish_rows == 1 || sh.finish_rows == 2 || sh.finish_rows == 4)
+                                    : (sh.finish_rows >= 1 && sh.finish_rows <= 64));
     // chunks of equal size cover all tiles; the finish launch's grid stays far below 2^31
     const uint64_t nchunks = ((uint64_t)a.tiles + sh.chunk_tiles - 1) / sh.chunk_tiles;
     EXPECT(nchunks * sh.chunk_tiles < (uint64_t)a.tiles + nchunks * 8u * (sh.chunk_tiles / sh.sub_tiles) + 8u);
