@@ -513,6 +513,44 @@ def test_steps_captured_in_a_graph_replay_correctly():
     eager.check("graph replays vs oracle")
 
 
+def test_large_groups_captured_in_a_graph(always_streaming):
+    """While a stream is being captured the split form is not used (its buffer is tied to a
+    stream, not to a graph, and may not be allocated then): the one-launch form is recorded.
+    The replays must continue the trajectory of eager calls, which do take the split form, bit
+    for bit."""
+    se.se_set_tuning("split", 1)
+    n, P, K = 16, 66000, 4
+    eager, graphed, warm = Case(n, P), Case(n, P), Case(n, P)
+    offs = eager.offsets()
+    grads = [torch.from_numpy(wl.host_grads(n, P, 1e-2, 0, t)).cuda() for t in range(K)]
+    side = torch.cuda.Stream()
+    se.se_set_tuning("split", 0)                    # warm the one-launch variants outside the capture
+    se.se_step(warm.dx, grads[0], warm.dv, offs, n, n, 0, 0.1, 0.9, side)
+    se.se_ring_step(warm.dx, grads[0], warm.dv, offs, n, 0.1, 0.9, side)
+    se.se_set_tuning("split", 1)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for t in range(K):
+            se.se_step(graphed.dx, grads[t], graphed.dv, offs, n, n, t, 0.1, 0.9, torch.cuda.current_stream())
+            se.se_ring_step(graphed.dx, grads[t], graphed.dv, offs, n, 0.1, 0.9, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for replay in range(3):
+        graph.replay()
+        for t in range(K):
+            se.se_step(eager.dx, grads[t], eager.dv, offs, n, n, t, 0.1, 0.9)
+            se.se_ring_step(eager.dx, grads[t], eager.dv, offs, n, 0.1, 0.9)
+        torch.cuda.synchronize()
+        assert torch.equal(eager.dx, graphed.dx) and torch.equal(eager.dv, graphed.dv), replay
+        (eager.dx * 1.0).sum().item()
+    for _ in range(3):
+        for t in range(K):
+            hg = grads[t].cpu().numpy()
+            oracle.step(eager.hx, hg, eager.hv, n, t, 0.1, 0.9)
+            oracle.ring_step(eager.hx, hg, eager.hv, 0.1, 0.9)
+    eager.check("large groups: graph replays vs oracle")
+
+
 def test_resume_from_any_iteration():
     """The plan is a pure function of (seed, n, iter): 0..7 in one go equals 0..3 then 4..7."""
     a, b = Case(16, 5000), Case(16, 5000)
