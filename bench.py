@@ -478,7 +478,16 @@ def main():
                                      "buckets_of_1Mi_elements": len(buckets),
                                      "steps_per_s_in_buckets": round(lsteps / bwall, 3)}
         out["all_workloads"] = {}
-        for name in ("tiny", "resnet20", "resnet50", "vgg16", "bert_base", "bert_base_full"):
+        # the paper's own four networks (Sec. 4.1) at its 16 workers in 4 groups: its
+        # communication-time model (Sec. 2.2, 3.1) on each layer list, 1 Gbps Ethernet
+        out["paper_context"]["comm_model_paper_networks"] = {}
+        for name in ("resnet18", "resnet50", "densenet121", "vgg16"):
+            pw = wl.WORKLOADS[name]
+            r = se.se_comm_model(pw.layer_offsets(), 4, 16, 4, 125e6, 1e-4)
+            out["paper_context"]["comm_model_paper_networks"][name] = {
+                "tensors": len(pw.sizes), "ring_s": round(r["ring_seconds"], 4), "sesgd_s": round(r["sesgd_seconds"], 4),
+                "ring_handshakes": r["ring_handshakes"], "sesgd_handshakes": r["sesgd_handshakes"]}
+        for name in ("tiny", "resnet20", "resnet18", "densenet121", "resnet50", "vgg16", "bert_base", "bert_base_full"):
             out["all_workloads"][name] = measure_workload(
                 name, args.steps, args.warmup, 0.0 if args.skip_cpu_baseline else 1.0, torch, se, wl)
     print(json.dumps(out), flush=True)

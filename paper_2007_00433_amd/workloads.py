@@ -52,6 +52,40 @@ def resnet50_sizes() -> List[int]:
     return sizes
 
 
+def resnet18_sizes() -> List[int]:
+    """ImageNet ResNet-18: 7x7 stem, stages of 2/2/2/2 basic blocks (two 3x3 convs each) of
+    width 64/128/256/512, a 1x1 projection shortcut in the first block of stages 2-4, BN after
+    every conv, 512x1000 FC + bias."""
+    sizes = [7 * 7 * 3 * 64, 64, 64]
+    c_in = 64
+    for width in (64, 128, 256, 512):
+        for b in range(2):
+            sizes += [c_in * width * 9, width, width]
+            sizes += [width * width * 9, width, width]
+            if b == 0 and c_in != width:
+                sizes += [c_in * width, width, width]
+            c_in = width
+    sizes += [512 * 1000, 1000]
+    return sizes
+
+
+def densenet121_sizes() -> List[int]:
+    """ImageNet DenseNet-121: 7x7 stem to 64 channels + BN, dense blocks of 6/12/24/16 layers
+    (BN, 1x1 conv to 128, BN, 3x3 conv to 32 new channels), transitions (BN, 1x1 conv halving
+    the channels) between them, a final BN, 1024x1000 classifier + bias."""
+    sizes = [7 * 7 * 3 * 64, 64, 64]
+    c = 64
+    for bi, layers in enumerate((6, 12, 24, 16)):
+        for _ in range(layers):
+            sizes += [c, c, c * 128, 128, 128, 128 * 32 * 9]
+            c += 32
+        if bi < 3:
+            sizes += [c, c, c * (c // 2)]
+            c //= 2
+    sizes += [c, c, c * 1000, 1000]
+    return sizes
+
+
 def vgg16_sizes() -> List[int]:
     """VGG-16: 13 3x3 convs with bias, then FC 25088x4096, 4096x4096, 4096x1000 with bias."""
     sizes = []
@@ -122,6 +156,9 @@ WORKLOADS = {
     "resnet20": _wl("resnet20", 16, 4, resnet20_sizes(), grad_std=1e-2, iters=100),
     "resnet50": _wl("resnet50", 16, 4, resnet50_sizes(), grad_std=1e-3, iters=50),
     "vgg16": _wl("vgg16", 32, 4, vgg16_sizes(), grad_std=1e-3, iters=20),
+    # the other two networks of the paper's experiments (Sec. 4.1), at its 16 workers in 4 groups
+    "resnet18": _wl("resnet18", 16, 4, resnet18_sizes(), grad_std=1e-3, iters=10),
+    "densenet121": _wl("densenet121", 16, 4, densenet121_sizes(), grad_std=1e-3, iters=10),
     "bert_base": _wl("bert_base", 64, 8, bert_base_sizes(), grad_std=1e-3, lr=1e-4,
                      iters=10, grad_dtype="bf16"),
     "bert_base_full": _wl("bert_base_full", 64, 64, bert_base_sizes(), grad_std=1e-3,

@@ -730,6 +730,14 @@ def test_full_size_bert_one_group_of_64_equals_ring_sgd():
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("name", ["resnet18", "densenet121"])
+def test_full_size_other_networks_of_the_paper_sampled(name):
+    """The two further networks of the paper's experiments (Sec. 4.1) at its 16 workers in 4
+    groups: 10 iterations of the step and of the Ring-SGD baseline at full size."""
+    _full_size_sampled(name, 10)
+    _full_size_sampled(name, 3, ring=True)
+
+
 @pytest.mark.parametrize("group_size", [1, 2, 16])
 def test_full_size_resnet50_other_group_sizes_sampled(group_size):
     """The residency of the launch is chosen per group size; each choice at full size."""
