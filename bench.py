@@ -362,6 +362,14 @@ def main():
         out["ring_baseline"] = {"value": round(args.steps / rwall, 3), "unit": "steps/s",
                                 "achieved_gbs": round(bytes_per_launch / rper / 1e9, 1),
                                 "frac": round(bytes_per_launch / rper / 1e9 / HBM_PEAK_GBS, 4)}
+    if not args.skip_copy and len(pool) > 1:
+        # one direction only: what the memory system gives to reads and to writes apart from their mix
+        a_buf, b_buf = pool[0].reshape(-1), pool[1].reshape(-1)
+        _, rper = timed_steps(lambda t, stream: se.se_calib_oneway(b_buf, a_buf, nb, 1, stream), 10, 3, torch)
+        _, wper = timed_steps(lambda t, stream: se.se_calib_oneway(b_buf, a_buf, nb, 2, stream), 10, 3, torch)
+        out["copy_ceiling"]["read_only_gbs"] = round(nb / rper / 1e9, 1)
+        out["copy_ceiling"]["write_only_gbs"] = round(nb / wper / 1e9, 1)
+        pool[1].normal_(0, w.grad_std)             # the writer left a pattern behind
     # Context only (other hardware, end-to-end training, not this path's metric): what the
     # paper reports, and its own communication-time model evaluated on this layer list.
     model = {}

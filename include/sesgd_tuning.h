@@ -18,6 +18,12 @@ extern "C" {
  * byte counters and a practical bandwidth ceiling next to se_step's figure. */
 int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
 
+/* Measurement helper: one direction only, between the same kind of buffers as se_calib_copy.
+ * direction 1 reads nbytes from src and writes nothing; direction 2 writes nbytes of a constant
+ * pattern to dst (its contents are lost) and reads nothing.  Tells what the memory system gives
+ * to reads and to writes apart from what it gives to their mix. */
+int se_calib_oneway(void *dst, const void *src, int64_t nbytes, int direction, void *stream);
+
 /* Launch-shape knobs for measurement sweeps; results never depend on them (process-wide).
  *   "max_blocks_per_cu"   one-launch forms: cap on resident workgroups per compute unit, enforced
  *                         by requesting 160 KiB / cap of (unused) LDS per workgroup; 0 = no cap;

@@ -27,7 +27,7 @@ SE_MAX_WORKERS = 64
 
 EXPORTS = ("se_plan", "se_plan_noalloc", "se_plan_device", "se_step", "se_step_bf16g", "se_ring_step",
            "se_ring_step_bf16g", "se_set_seed", "se_get_seed", "se_pitch", "se_step_bytes",
-           "se_set_tuning", "se_get_tuning", "se_strerror", "se_last_error", "se_calib_copy",
+           "se_set_tuning", "se_get_tuning", "se_strerror", "se_last_error", "se_calib_copy", "se_calib_oneway",
            "se_step_ex", "se_global_average", "se_consensus", "se_comm_model")
 
 
@@ -95,6 +95,8 @@ def _load() -> ctypes.CDLL:
                                   vp, vp, vp, vp]
     lib.se_calib_copy.restype = i32
     lib.se_calib_copy.argtypes = [vp, vp, i64, vp]
+    lib.se_calib_oneway.restype = i32
+    lib.se_calib_oneway.argtypes = [vp, vp, i64, i32, vp]
     lib.se_strerror.restype = cp
     lib.se_strerror.argtypes = [i32]
     lib.se_last_error.restype = cp
@@ -198,6 +200,16 @@ def se_calib_copy(dst, src, nbytes: int, stream=None) -> None:
     check(lib.se_calib_copy(_rows(dst, 0, 0, dst.element_size() if hasattr(dst, "element_size") else 1, "dst"),
                             _rows(src, 0, 0, src.element_size() if hasattr(src, "element_size") else 1, "src"),
                             nbytes, _stream(stream)))
+
+
+def se_calib_oneway(dst, src, nbytes: int, direction: int, stream=None) -> None:
+    """direction 1: read nbytes of src; direction 2: overwrite nbytes of dst with a pattern."""
+    for buf, what in ((dst, "dst"), (src, "src")):
+        if hasattr(buf, "data_ptr") and buf.numel() * buf.element_size() < nbytes:
+            raise ValueError(f"{what} is shorter than {nbytes} bytes")
+    check(lib.se_calib_oneway(_rows(dst, 0, 0, dst.element_size() if hasattr(dst, "element_size") else 1, "dst"),
+                              _rows(src, 0, 0, src.element_size() if hasattr(src, "element_size") else 1, "src"),
+                              nbytes, direction, _stream(stream)))
 
 
 def se_plan_raw(n, group_size, it, group_of_ptr, members_ptr) -> int:

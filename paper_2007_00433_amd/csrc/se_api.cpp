@@ -436,6 +436,18 @@ int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream)
     return e == hipSuccess ? SE_OK : hip_fail("se_calib_copy launch", e);
 }
 
+int se_calib_oneway(void *dst, const void *src, int64_t nbytes, int direction, void *stream)
+{
+    if (nbytes < 0 || (direction != 1 && direction != 2)) return SE_ERR_ARG;
+    if (!dst || !src) return SE_ERR_NULL;
+    if ((uintptr_t)dst % 16 || (uintptr_t)src % 16 || nbytes % 16 || nbytes >= ((int64_t)1 << 37) ||
+        overlaps(dst, (uint64_t)nbytes, src, (uint64_t)nbytes))
+        return SE_ERR_LAYOUT;
+    if (nbytes == 0) return SE_OK;
+    const hipError_t e = se::launch_calib_oneway(dst, src, (uint64_t)nbytes, direction, (hipStream_t)stream);
+    return e == hipSuccess ? SE_OK : hip_fail("se_calib_oneway launch", e);
+}
+
 int se_set_seed(uint64_t seed) { g_seed.store(seed); return SE_OK; }
 uint64_t se_get_seed(void) { return g_seed.load(); }
 

@@ -80,6 +80,9 @@ hipError_t launch_consensus(const float *x, uint64_t pitch_elems, uint64_t ncols
 hipError_t launch_calib_copy(void *dst, const void *src, uint64_t nbytes, int policy,
                              hipStream_t stream);
 
+// mode 1: read nbytes from src only; mode 2: write nbytes to dst only (a constant pattern)
+hipError_t launch_calib_oneway(void *dst, const void *src, uint64_t nbytes, int mode, hipStream_t stream);
+
 // Lets `kernel` request up to the whole LDS of a compute unit as dynamic shared memory; done
 // once per device (bit per device ordinal in `done`).
 inline hipError_t allow_full_lds(const void *kernel, std::atomic<uint64_t> &done)

@@ -88,6 +88,7 @@ hipError_t launch_plan(uint64_t, int64_t, int, int, int32_t *, int32_t *, hipStr
 hipError_t plan_to_host_noalloc(uint64_t, int64_t, int, int, int32_t *, int32_t *) { return hipSuccess; }
 hipError_t launch_consensus(const float *, uint64_t, uint64_t, int, double *, hipStream_t) { return hipSuccess; }
 hipError_t launch_calib_copy(void *, const void *, uint64_t, int, hipStream_t) { return hipSuccess; }
+hipError_t launch_calib_oneway(void *, const void *, uint64_t, int, hipStream_t) { return hipSuccess; }
 }  // namespace se
 
 // The launches recorded since `from` must cover columns [c0, c1) of the row that starts at

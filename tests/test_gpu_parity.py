@@ -513,6 +513,30 @@ def test_steps_captured_in_a_graph_replay_correctly():
     eager.check("graph replays vs oracle")
 
 
+def test_calibration_kernels_move_exactly_what_they_say():
+    """The measurement helpers: the copy copies, the reader changes nothing, the writer writes
+    its pattern to exactly the bytes asked for (sizes off the 4 KiB piece of a wavefront)."""
+    for nfloats in (4, 1020, 1024, 1028, 70000 * 4):
+        src = torch.randn(nfloats + 8, device="cuda")
+        dst = torch.full((nfloats + 8,), -5.0, device="cuda")
+        keep = src.clone()
+        se.se_calib_copy(dst, src, nfloats * 4)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:nfloats], src[:nfloats]) and (dst[nfloats:] == -5.0).all().item()
+        dst.fill_(-5.0)
+        se.se_calib_oneway(dst, src, nfloats * 4, 1)
+        torch.cuda.synchronize()
+        assert torch.equal(src, keep) and (dst == -5.0).all().item()
+        se.se_calib_oneway(dst, src, nfloats * 4, 2)
+        torch.cuda.synchronize()
+        assert torch.equal(src, keep) and (dst[nfloats:] == -5.0).all().item()
+        got = dst[:nfloats].view(-1, 4)
+        assert (got[:, 0] == 1.0).all().item() and (got[:, 1] == 2.0).all().item() and (got[:, 2] == 3.0).all().item()
+        assert ((got[:, 3] >= 0.0) & (got[:, 3] <= 3.0)).all().item()
+    with pytest.raises(se.SesgdError):
+        se.se_calib_oneway(dst, src, 64, 3)
+
+
 def test_large_groups_captured_in_a_graph(always_streaming):
     """While a stream is being captured the split form is not used (its buffer is tied to a
     stream, not to a graph, and may not be allocated then): the one-launch form is recorded.
