@@ -34,7 +34,8 @@ int se_calib_oneway(void *dst, const void *src, int64_t nbytes, int direction, v
  *                         "cache_resident_mib"
  *   "batch_rows"          single-wavefront SESGD update: member rows whose loads are issued back
  *                         to back (1, 2, 4, 8); 0 (default) = 1 for groups up to 4, 2 up to 8, 8
- *                         beyond; all rows of a small group at once below "cache_resident_mib"
+ *                         beyond; all rows of a small group at once below "cache_resident_mib";
+ *                         also the rows per batch of the split form's first launch (default 1)
  *   "nontemporal"         cache policy of the row accesses: 0 plain; 1 streaming (non-temporal)
  *                         loads and stores; 2 (default) streaming, and stores written through
  *                         the L2 to memory at once (measured 2-4 % faster than 1)
@@ -56,7 +57,7 @@ int se_calib_oneway(void *dst, const void *src, int64_t nbytes, int direction, v
  *                         = 4096 when gradients are averaged, 2048 otherwise
  *   "split_cap_reduce", "split_cap_finish"   resident workgroups per compute unit of its first
  *                         and second launch; 0 = no cap; -1 (default) = 12 and 24 when gradients
- *                         are averaged, else 4 (6 with bf16 gradients) and 16
+ *                         are averaged, else 7 (10 with bf16 gradients) and 16
  *   "split_finish_rows"   rows per wavefront of its second launch: 1, 2 or 4 when gradients are
  *                         averaged, a multiple of 8 otherwise; 0 (default) = 1 and 8
  * Returns SE_ERR_ARG for an unknown name or a value out of range. */

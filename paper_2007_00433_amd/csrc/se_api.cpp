@@ -211,12 +211,14 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
             else if (j.mode == se::kAvgOnly) fr = fr < 1 ? 1 : fr;
             else fr = fr < 8 ? 8 : fr / 8 * 8;
             sh.finish_rows = fr;
+            sh.reduce_batch = g_batch_rows.load() > 0 ? g_batch_rows.load() : 1;
             // Resident workgroups per CU, from sweeps on the ResNet-50, VGG-16 and BERT shapes:
             // the mean-gradient pass has 8 KiB or less in flight per wavefront and wants 12 or
-            // more, the one-row update 24; the 8-row SESGD pass 4 (6 with bf16 gradients),
-            // the pass that writes the mean 16.
+            // more, the one-row update 24; the 8-row SESGD pass, walked one row at a time like the
+            // single-wavefront form, 7 (10 with bf16 gradients; all 8 rows at once with 4 to 6
+            // workgroups measured 1-4 % slower), the pass that writes the mean 16.
             int cr = g_split_cap_reduce.load(), cf = g_split_cap_finish.load();
-            if (cr < 0) cr = j.mode != se::kSesgd ? 12 : j.grad_bytes == 2 ? 6 : 4;
+            if (cr < 0) cr = j.mode != se::kSesgd ? 12 : j.grad_bytes == 2 ? 10 : 7;
             if (cf < 0) cf = j.mode != se::kSesgd ? 24 : 16;
             sh.lds_reduce = cr > 0 ? (se::kLdsPerCu / (uint32_t)cr) & ~1023u : 0u;
             sh.lds_finish = cf > 0 ? (se::kLdsPerCu / (uint32_t)cf) & ~1023u : 0u;

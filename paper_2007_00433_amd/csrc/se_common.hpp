@@ -55,6 +55,7 @@ struct SplitShape {
     uint32_t sub_tiles;     // tiles per sub-chunk of the finish launch
     int finish_rows;        // rows per wavefront of the finish launch: 1, 2, 4 when gradients are
                             // averaged, a multiple of 8 otherwise
+    int reduce_batch;       // SESGD update: rows of a block loaded back to back in the first launch (2 or 8)
     uint32_t lds_reduce;    // dynamic LDS of the two launches, only to cap residency (0 = none)
     uint32_t lds_finish;
 };

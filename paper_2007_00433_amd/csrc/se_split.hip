@@ -53,7 +53,7 @@ __device__ __forceinline__ uint64_t skip_members(uint64_t mask, int skip)
     return mask;
 }
 
-template <bool BF16, bool HAS_V, bool HAS_WD, int NT, int MODE>
+template <bool BF16, bool HAS_V, bool HAS_WD, int NT, int MODE, int BMAX>
 __global__ __launch_bounds__(64) void se_split_reduce_kernel(const SplitArgs q)
 {
     const StepArgs &p = q.a;
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(64) void se_split_reduce_kernel(const SplitArgs q)
         uint64_t todo = skip_members(members, b * kSumBlock);
         const int count = min(kSumBlock, p.m - b * kSumBlock);           // one block: a single partial
 #define SE_CALL(B, F, ACC) sesgd_batch<kVec, BF16, HAS_V, HAS_WD, NT, B, F>(p, todo, off, goff, gpitch_bytes, ACC)
-        SE_SUM_MEMBER_BLOCKS(8, count, kVec, s, SE_CALL);
+        SE_SUM_MEMBER_BLOCKS(BMAX, count, kVec, s, SE_CALL);
 #undef SE_CALL
     }
     // plain store: the value is wanted again soon, from cache
@@ -201,10 +201,10 @@ template <typename K> static hipError_t cap_residency(K kern, std::atomic<uint64
     return lds > 0 ? allow_full_lds((const void *)kern, allowed) : hipSuccess;
 }
 
-template <bool BF16, bool HAS_V, bool HAS_WD, int NT, int MODE>
+template <bool BF16, bool HAS_V, bool HAS_WD, int NT, int MODE, int BMAX>
 static hipError_t launch_chunks(const StepArgs &a, const SplitShape &sh, hipStream_t stream)
 {
-    auto reduce = se_split_reduce_kernel<BF16, HAS_V, HAS_WD, NT, MODE>;
+    auto reduce = se_split_reduce_kernel<BF16, HAS_V, HAS_WD, NT, MODE, BMAX>;
     auto finish = se_split_finish_kernel<HAS_V, HAS_WD, NT, MODE>;
     static std::atomic<uint64_t> allowed_r{0}, allowed_f{0};
     hipError_t e = cap_residency(reduce, allowed_r, sh.lds_reduce);
@@ -239,10 +239,25 @@ template <bool BF16, int NT, int MODE>
 static hipError_t launch_flags(const StepArgs &a, const SplitShape &sh, hipStream_t stream)
 {
     const bool has_v = a.v != nullptr, has_wd = a.wd != 0.0f;
-    if (has_v) return has_wd ? launch_chunks<BF16, true, true, NT, MODE>(a, sh, stream)
-                             : launch_chunks<BF16, true, false, NT, MODE>(a, sh, stream);
-    return has_wd ? launch_chunks<BF16, false, true, NT, MODE>(a, sh, stream)
-                  : launch_chunks<BF16, false, false, NT, MODE>(a, sh, stream);
+    if constexpr (MODE == kSesgd) {
+        // rows of a block whose loads are issued back to back in the first launch
+        if (sh.reduce_batch < 2) {
+            if (has_v) return has_wd ? launch_chunks<BF16, true, true, NT, MODE, 1>(a, sh, stream)
+                                     : launch_chunks<BF16, true, false, NT, MODE, 1>(a, sh, stream);
+            return has_wd ? launch_chunks<BF16, false, true, NT, MODE, 1>(a, sh, stream)
+                          : launch_chunks<BF16, false, false, NT, MODE, 1>(a, sh, stream);
+        }
+        if (sh.reduce_batch < 8) {
+            if (has_v) return has_wd ? launch_chunks<BF16, true, true, NT, MODE, 2>(a, sh, stream)
+                                     : launch_chunks<BF16, true, false, NT, MODE, 2>(a, sh, stream);
+            return has_wd ? launch_chunks<BF16, false, true, NT, MODE, 2>(a, sh, stream)
+                          : launch_chunks<BF16, false, false, NT, MODE, 2>(a, sh, stream);
+        }
+    }
+    if (has_v) return has_wd ? launch_chunks<BF16, true, true, NT, MODE, 8>(a, sh, stream)
+                             : launch_chunks<BF16, true, false, NT, MODE, 8>(a, sh, stream);
+    return has_wd ? launch_chunks<BF16, false, true, NT, MODE, 8>(a, sh, stream)
+                  : launch_chunks<BF16, false, false, NT, MODE, 8>(a, sh, stream);
 }
 
 template <bool BF16, int NT>
@@ -253,7 +268,7 @@ static hipError_t launch_mode(const StepArgs &a, const SplitShape &sh, hipStream
     case kGradAvg: return launch_flags<BF16, NT, kGradAvg>(a, sh, stream);
     default:
         if constexpr (BF16) return hipErrorInvalidValue;
-        else return launch_chunks<false, false, false, NT, kAvgOnly>(a, sh, stream);
+        else return launch_chunks<false, false, false, NT, kAvgOnly, 8>(a, sh, stream);
     }
 }
 
