@@ -29,13 +29,16 @@ int se_calib_oneway(void *dst, const void *src, int64_t nbytes, int direction, v
  *                         by requesting 160 KiB / cap of (unused) LDS per workgroup; 0 = no cap;
  *                         -1 (default) = the measured optimum per launch: 16, 12, 8 for group
  *                         sizes 1, 2, 4 (11 for 4 with bf16 gradients), 5 up to 8 rows (6 with
- *                         bf16 gradients), 2 beyond, 2 for gradient averaging, 4 for the global
- *                         average, 8 for the LDS-staged form; none for calls below
+ *                         bf16 gradients), 2 beyond; one-launch gradient averaging 8 for up to 4
+ *                         workers, 4 or 8 up to 8, 6 beyond; the global average 12, 8, 4 for up to
+ *                         2, 4, more workers; 8 for the LDS-staged form; none for calls below
  *                         "cache_resident_mib"
  *   "batch_rows"          single-wavefront SESGD update: member rows whose loads are issued back
  *                         to back (1, 2, 4, 8); 0 (default) = 1 for groups up to 4, 2 up to 8, 8
  *                         beyond; all rows of a small group at once below "cache_resident_mib";
  *                         also the rows per batch of the split form's first launch (default 1)
+ *                         and of the update pass of one-launch gradient averaging (default 1,
+ *                         2 for 5-8 workers with fp32 gradients)
  *   "nontemporal"         cache policy of the row accesses: 0 plain; 1 streaming (non-temporal)
  *                         loads and stores; 2 (default) streaming, and stores written through
  *                         the L2 to memory at once (measured 2-4 % faster than 1)

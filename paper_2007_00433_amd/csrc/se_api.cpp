@@ -89,21 +89,31 @@ struct Job {
 // scatter the tiles in flight; rows of bf16 gradients are shorter and want a few more.
 int auto_batch_rows(const Job &j, bool streams, uint64_t launch_bytes)
 {
-    if (j.mode != se::kSesgd) return 8;
+    if (j.mode == se::kAvgOnly) return 8;
     // Buffers small enough for plain accesses: all rows of a small group at once is 0-5 % faster.
     // Launches over few columns (a layer range) are over before the order of the rows matters;
     // there one round trip for all rows is what counts (161 per-tensor launches of the
     // ResNet-50 shape: 566 against 530 steps/s).
-    if (!streams || launch_bytes < ((uint64_t)64 << 20)) return j.m >= 8 ? 8 : 4;
+    if (!streams || launch_bytes < ((uint64_t)64 << 20)) return j.mode == se::kSesgd && j.m < 8 ? 4 : 8;
+    if (j.mode == se::kGradAvg)           // rows per batch of the second pass (update of v and x)
+        return j.m <= 4 ? 1 : j.m <= 8 ? (j.grad_bytes == 2 ? 1 : 2) : 1;
     return j.m <= 4 ? 1 : j.m <= 8 ? 2 : 8;
 }
 
 int auto_blocks_per_cu(const Job &j, int batch)
 {
-    if (j.mode == se::kGradAvg) return 2;
-    if (j.mode == se::kAvgOnly) return 4;
-    if (j.m > 8) return 2;
     const bool bf16 = j.grad_bytes == 2;
+    if (j.mode == se::kGradAvg) {
+        // one-launch gradient averaging (rings of up to 8 workers, and larger ones below the
+        // split form's size): 6.54 TB/s for 4 workers one row at a time with 8 workgroups per CU
+        // (all 4 rows at once with 2: 4.52), 6.31 for 8 workers two rows at a time with 4
+        if (batch >= 8) return j.m <= 4 ? 6 : 2;
+        if (j.m <= 4) return 8;
+        if (j.m <= 8) return batch == 1 ? 8 : 4;
+        return 6;
+    }
+    if (j.mode == se::kAvgOnly) return j.m <= 2 ? 12 : j.m <= 4 ? 8 : 4;   // 4 workers: 6.65 TB/s with 8, 4.90 with 4
+    if (j.m > 8) return 2;
     if (batch >= 8) return 4;
     if (batch >= 4) return 6;
     if (j.m == 1) return 16;

@@ -65,7 +65,7 @@ __global__ __launch_bounds__(64) void se_step_kernel(const StepArgs p)
     todo = members;
     if constexpr (MODE == kGradAvg) {
 #define SE_CALL(B, F) update_batch<VEC, HAS_V, HAS_WD, NT, B, F>(p, todo, off, mean)
-        SE_FOR_MEMBER_BATCHES(8, p.m, SE_CALL);
+        SE_FOR_MEMBER_BATCHES(BMAX, p.m, SE_CALL);
 #undef SE_CALL
     } else {
         while (todo)
@@ -110,6 +110,9 @@ static hipError_t launch_mode(const StepArgs &a, const LaunchShape &s, hipStream
         return launch_flags<VEC, BF16, NT, kSesgd, 1>(a, s, stream);
     }
     case kGradAvg:
+        // rows updated per batch in the second pass (the first pass adds the gradients up 8 rows at a time)
+        if (s.batch_rows == 1) return launch_flags<VEC, BF16, NT, kGradAvg, 1>(a, s, stream);
+        if (s.batch_rows == 2) return launch_flags<VEC, BF16, NT, kGradAvg, 2>(a, s, stream);
         return launch_flags<VEC, BF16, NT, kGradAvg, 8>(a, s, stream);
     default:
         if constexpr (BF16) return hipErrorInvalidValue;
