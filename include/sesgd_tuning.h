@@ -27,11 +27,13 @@ int se_calib_oneway(void *dst, const void *src, int64_t nbytes, int direction, v
 /* Launch-shape knobs for measurement sweeps; results never depend on them (process-wide).
  *   "max_blocks_per_cu"   one-launch forms: cap on resident workgroups per compute unit, enforced
  *                         by requesting 160 KiB / cap of (unused) LDS per workgroup; 0 = no cap;
- *                         -1 (default) = the measured optimum per launch: 16, 12, 8 for group
- *                         sizes 1, 2, 4 (11 for 4 with bf16 gradients), 5 up to 8 rows (6 with
- *                         bf16 gradients), 2 beyond; one-launch gradient averaging 8 for up to 4
- *                         workers, 4 or 8 up to 8, 6 beyond; the global average 12, 8, 4 for up to
- *                         2, 4, more workers; 8 for the LDS-staged form; none for calls below
+ *                         -1 (default) = chosen per launch so that about 48 / 32 / 24-36 KiB of
+ *                         loads are in flight per compute unit for groups of 1 / 2 / more rows:
+ *                         16, 11, 9 workgroups for group sizes 1, 2, 4 with momentum and fp32
+ *                         gradients, more for shorter rows (bf16 gradients, no momentum buffer),
+ *                         4 for groups of 8 walked two rows at a time, 2 beyond 8 rows (6 for
+ *                         gradient averaging); the global average 12, 8, 4 for up to 2, 4, more
+ *                         workers; 8 for the LDS-staged form; none for calls below
  *                         "cache_resident_mib"
  *   "batch_rows"          single-wavefront SESGD update: member rows whose loads are issued back
  *                         to back (1, 2, 4, 8); 0 (default) = 1 for groups up to 4, 2 up to 8, 8
@@ -60,7 +62,8 @@ int se_calib_oneway(void *dst, const void *src, int64_t nbytes, int direction, v
  *                         = 4096 when gradients are averaged, 2048 otherwise
  *   "split_cap_reduce", "split_cap_finish"   resident workgroups per compute unit of its first
  *                         and second launch; 0 = no cap; -1 (default) = 12 and 24 when gradients
- *                         are averaged, else 7 (10 with bf16 gradients) and 16
+ *                         are averaged, else 7 (10 with bf16 gradients) and 16; without a
+ *                         momentum buffer 10 and 32, else twice as many and 8
  *   "split_finish_rows"   rows per wavefront of its second launch: 1, 2 or 4 when gradients are
  *                         averaged, a multiple of 8 otherwise; 0 (default) = 1 and 8
  * Returns SE_ERR_ARG for an unknown name or a value out of range. */

@@ -81,12 +81,14 @@ struct Job {
     hipStream_t stream;
 };
 
-// Rows a wavefront of the single-wavefront SESGD update loads back to back, and resident
-// workgroups per CU, from sweeps on MI355X (ResNet-50, VGG-16 and BERT shapes; fp32 and bf16
-// gradients; n = 16, 32, 64).  One row at a time (x, g, v of one member, then the next) with 8
-// workgroups per CU measured 1-3 % faster for groups of 4 than all 4 rows at once with 6; groups
-// of 5 to 8 run best two rows at a time.  Fewer workgroups starve the memory system, more
-// scatter the tiles in flight; rows of bf16 gradients are shorter and want a few more.
+// Launch shape of the one-launch forms on buffers that stream from HBM, from sweeps on MI355X
+// (ResNet-50-, VGG-16- and BERT-sized rows; fp32 and bf16 gradients; with and without a momentum
+// buffer; 4 to 64 workers; all group sizes up to 8).
+//
+// Rows per batch: a wavefront issues the loads of `batch` member rows (x, g, v of each) back to
+// back, then does their arithmetic and stores.  One row at a time measured 1-3 % faster for
+// groups of up to 4 than all rows at once, two at a time for groups of 5 to 8: fewer rows open
+// per wavefront at a time.  The same holds for the update pass of gradient averaging.
 int auto_batch_rows(const Job &j, bool streams, uint64_t launch_bytes)
 {
     if (j.mode == se::kAvgOnly) return 8;
@@ -95,31 +97,34 @@ int auto_batch_rows(const Job &j, bool streams, uint64_t launch_bytes)
     // there one round trip for all rows is what counts (161 per-tensor launches of the
     // ResNet-50 shape: 566 against 530 steps/s).
     if (!streams || launch_bytes < ((uint64_t)64 << 20)) return j.mode == se::kSesgd && j.m < 8 ? 4 : 8;
-    if (j.mode == se::kGradAvg)           // rows per batch of the second pass (update of v and x)
-        return j.m <= 4 ? 1 : j.m <= 8 ? (j.grad_bytes == 2 ? 1 : 2) : 1;
-    return j.m <= 4 ? 1 : j.m <= 8 ? 2 : 8;
+    if (j.m > 8) return j.mode == se::kGradAvg ? 1 : 8;
+    return j.m <= 4 ? 1 : 2;
 }
 
-int auto_blocks_per_cu(const Job &j, int batch)
+// Resident workgroups per CU.  What the sweeps have in common is the amount of loads in flight
+// per CU: about 48 KiB for singleton groups, 32 KiB for pairs, 25-28 KiB for larger groups (36 KiB
+// for groups of 5, whose batches are 2 + 2 + 1 rows, and for gradient averaging over 3, 5 or 6
+// rows), whatever the bytes per row (momentum buffer
+// or not, fp32 or bf16 gradients, 128-, 64- or 32-bit accesses): 16 / 11 / 8 workgroups for
+// groups of 1 / 2 / 4 with momentum and fp32 gradients, 10 for groups of 4 with bf16 gradients,
+// 24 / 16 / 13 without a momentum buffer, 4 to 6 for groups of 8 two rows at a time.  Fewer
+// starve the memory system, more scatter the tiles in flight and lose DRAM locality.
+int auto_blocks_per_cu(const Job &j, int batch, int vec)
 {
-    const bool bf16 = j.grad_bytes == 2;
-    if (j.mode == se::kGradAvg) {
-        // one-launch gradient averaging (rings of up to 8 workers, and larger ones below the
-        // split form's size): 6.54 TB/s for 4 workers one row at a time with 8 workgroups per CU
-        // (all 4 rows at once with 2: 4.52), 6.31 for 8 workers two rows at a time with 4
-        if (batch >= 8) return j.m <= 4 ? 6 : 2;
-        if (j.m <= 4) return 8;
-        if (j.m <= 8) return batch == 1 ? 8 : 4;
-        return 6;
-    }
     if (j.mode == se::kAvgOnly) return j.m <= 2 ? 12 : j.m <= 4 ? 8 : 4;   // 4 workers: 6.65 TB/s with 8, 4.90 with 4
-    if (j.m > 8) return 2;
-    if (batch >= 8) return 4;
-    if (batch >= 4) return 6;
-    if (j.m == 1) return 16;
-    if (j.m == 2) return 12;
-    if (j.m <= 4) return bf16 ? 11 : 8;
-    return bf16 ? 6 : 5;                      // 5 to 8 rows, two at a time
+    if (j.m > 8) return j.mode == se::kGradAvg ? 6 : 2;
+    if (batch > j.m) batch = j.m;
+    const int row_bytes = 64 * vec * (4 + j.grad_bytes + (j.v ? 4 : 0));
+    if (batch >= 4) {
+        // all rows of the group at once (small launches, or on request): about 72 KiB in flight
+        const int all = 72 * 1024 / (batch * row_bytes);
+        return all < 4 ? 4 : all > 16 ? 16 : all;
+    }
+    int target_kib = j.m == 1 ? 48 : j.m == 2 ? 32 : j.m <= 4 ? 25 : j.m == 5 ? 36 : 28;
+    if (j.mode == se::kGradAvg && (j.m == 3 || j.m == 5 || j.m == 6)) target_kib = 36;
+    const int target = target_kib * 1024;
+    const int cap = (target + batch * row_bytes / 2) / (batch * row_bytes);
+    return cap < 2 ? 2 : cap > 24 ? 24 : cap;
 }
 
 // One launch over columns [c0, c1) with `vec` columns per lane; (c1 - c0) % vec == 0 and every
@@ -182,7 +187,7 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     const int coop = g_cooperative.load();
     const bool use_coop = coop > 0;
     int cap = g_max_blocks_per_cu.load();
-    if (cap < 0) cap = !streams ? 0 : use_coop ? 8 : auto_blocks_per_cu(j, s.batch_rows);
+    if (cap < 0) cap = !streams ? 0 : use_coop ? 8 : auto_blocks_per_cu(j, s.batch_rows, vec);
     s.lds_bytes = cap > 0 ? (se::kLdsPerCu / (uint32_t)cap) & ~1023u : 0u;
     // Split form: two launches per chunk of columns with an intermediate in a library-owned
     // buffer; for reductions over more than 8 rows on the 128-bit path.  Measured on MI355X it
@@ -226,10 +231,12 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
             // the mean-gradient pass has 8 KiB or less in flight per wavefront and wants 12 or
             // more, the one-row update 24; the 8-row SESGD pass, walked one row at a time like the
             // single-wavefront form, 7 (10 with bf16 gradients; all 8 rows at once with 4 to 6
-            // workgroups measured 1-4 % slower), the pass that writes the mean 16.
+            // workgroups measured 1-4 % slower), the pass that writes the mean 16.  Without a
+            // momentum buffer a row is a third shorter: twice as many in the 8-row pass and 8 in the
+            // pass that writes the mean (6.19 against 5.45 TB/s), 32 in the one-row update.
             int cr = g_split_cap_reduce.load(), cf = g_split_cap_finish.load();
-            if (cr < 0) cr = j.mode != se::kSesgd ? 12 : j.grad_bytes == 2 ? 10 : 7;
-            if (cf < 0) cf = j.mode != se::kSesgd ? 24 : 16;
+            if (cr < 0) cr = j.mode != se::kSesgd ? (j.v ? 12 : 10) : (j.grad_bytes == 2 ? 10 : 7) * (j.v ? 1 : 2);
+            if (cf < 0) cf = j.mode != se::kSesgd ? (j.v ? 24 : 32) : (j.v ? 16 : 8);
             sh.lds_reduce = cr > 0 ? (se::kLdsPerCu / (uint32_t)cr) & ~1023u : 0u;
             sh.lds_finish = cf > 0 ? (se::kLdsPerCu / (uint32_t)cf) & ~1023u : 0u;
             return se::launch_split(a, s, sh, j.stream);
