@@ -205,8 +205,9 @@ uint64_t se_get_seed(void);
 /* Recommended row pitch for P elements: P rounded up to a multiple of 1024 elements, so that
  * with a 4 KiB-aligned base every row starts 4 KiB aligned: the 128-bit path is taken and each
  * wavefront's 1 KiB piece of a row is 1 KiB aligned (measured on MI355X: 3-4 % more bandwidth
- * than rows that are only 256-byte aligned, 15 % more than unaligned rows).  Returns -1 for
- * P < 0. */
+ * than rows that are only 128-byte aligned, 20-25 % more than rows that start anywhere else; such
+ * rows still move 128 bits per lane as long as each starts on a 4-byte boundary).  Returns -1
+ * for P < 0. */
 int64_t se_pitch(int64_t P);
 
 /* Bytes the method itself moves per call over `columns` elements per worker (reads + writes

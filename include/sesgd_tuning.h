@@ -41,6 +41,10 @@ int se_calib_oneway(void *dst, const void *src, int64_t nbytes, int direction, v
  *                         also the rows per batch of the split form's first launch (default 1)
  *                         and of the update pass of one-launch gradient averaging (default 1,
  *                         2 for 5-8 workers with fp32 gradients)
+ *   "unaligned_wide"      1 (default): rows that do not line up on 16 bytes (a pitch that is no
+ *                         multiple of 4 elements, bases at different offsets) still move 128 bits
+ *                         per lane, as every row starts on a 4-byte boundary; 0: such rows take
+ *                         the 64- or 32-bit body
  *   "nontemporal"         cache policy of the row accesses: 0 plain; 1 streaming (non-temporal)
  *                         loads and stores; 2 (default) streaming, and stores written through
  *                         the L2 to memory at once (measured 2-4 % faster than 1)

@@ -34,7 +34,8 @@ EXPORTS = ("se_plan", "se_plan_noalloc", "se_plan_device", "se_step", "se_step_b
 SE_FLAG_GRAD_AVG = 1
 TUNING_KNOBS = ("max_blocks_per_cu", "nontemporal", "cooperative", "coop_tiles",
                 "cache_resident_mib", "split", "split_scratch_mib", "split_sub_tiles",
-                "split_cap_reduce", "split_cap_finish", "split_finish_rows", "batch_rows")
+                "split_cap_reduce", "split_cap_finish", "split_finish_rows", "batch_rows",
+                "unaligned_wide")
 
 
 class SesgdError(RuntimeError):

@@ -24,7 +24,8 @@ std::atomic<int> g_split_scratch_mib{128}; // size of the split form's intermedi
 std::atomic<int> g_split_sub_tiles{0};    // tiles per sub-chunk of the split form's finish launch (0 = by mode)
 std::atomic<int> g_split_cap_reduce{-1};  // resident workgroups per CU of the two launches (0 = no cap, -1 = default)
 std::atomic<int> g_split_cap_finish{-1};
-std::atomic<int> g_batch_rows{0};         // single-wavefront SESGD update: rows per batch of loads (0 = by group size)
+std::atomic<int> g_batch_rows{0};            // single-wavefront SESGD update: rows per batch of loads (0 = by group size)
+std::atomic<int> g_unaligned_wide{1};        // 128-bit accesses also for rows that are only 4-byte aligned
 std::atomic<int> g_split_finish_rows{0};  // rows per wavefront of the finish launch (0 = default)
 
 thread_local char t_last_error[256] = "";
@@ -128,7 +129,8 @@ int auto_blocks_per_cu(const Job &j, int batch, int vec)
 }
 
 // One launch over columns [c0, c1) with `vec` columns per lane; (c1 - c0) % vec == 0 and every
-// row of every buffer is vec-aligned at column c0.
+// row of every buffer is vec-aligned at column c0 (for vec == 4, 4-byte alignment of the other
+// rows is enough when row 0 of the parameters is 16-byte aligned there).
 hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
 {
     if (c1 <= c0) return hipSuccess;
@@ -246,7 +248,7 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     return se::launch_step(a, s, j.stream);
 }
 
-// Columns [c0, c1) of every row: the widest aligned body plus scalar head and tail columns.
+// Columns [c0, c1) of every row: the widest body the rows allow plus scalar head and tail columns.
 hipError_t launch_range(const Job &j, int64_t c0, int64_t c1)
 {
     if (c1 <= c0) return hipSuccess;
@@ -256,7 +258,25 @@ hipError_t launch_range(const Job &j, int64_t c0, int64_t c1)
     const uintptr_t eg = j.g ? (uintptr_t)j.g / (uintptr_t)gb : ex;
     for (int vec = 4; vec > 1; vec >>= 1) {
         const uintptr_t v = (uintptr_t)vec;
-        if (j.pitch % vec != 0 || ex % v != ev % v || ex % v != eg % v) continue;
+        if (j.pitch % vec != 0 || ex % v != ev % v || ex % v != eg % v) {
+            // Rows that do not line up on 16 bytes (a pitch that is no multiple of 4 elements,
+            // bases at different offsets) still take 128-bit accesses when each starts on a
+            // 4-byte boundary, which is all a multi-dword global access needs: fp32 rows always
+            // do, bf16 gradient rows when the pitch and their first column are even.  Measured
+            // against the 64- and 32-bit bodies these rows would otherwise get: see the tuning
+            // header.  Row 0 of the parameters is brought to a 16-byte boundary first.
+            const bool g16 = j.g && j.grad_bytes == 2;
+            const int64_t head = (int64_t)((4u - (ex + (uintptr_t)c0) % 4u) % 4u);
+            const bool dword_rows = !g16 || (j.pitch % 2 == 0 && (eg + (uintptr_t)(c0 + head)) % 2u == 0);
+            if (vec == 4 && g_unaligned_wide.load() > 0 && dword_rows && c1 - (c0 + head) >= 4) {
+                const int64_t a = c0 + head, b = a + (c1 - a) / 4 * 4;
+                hipError_t e = launch_columns(j, c0, a, 1);
+                if (e == hipSuccess) e = launch_columns(j, a, b, 4);
+                if (e == hipSuccess) e = launch_columns(j, b, c1, 1);
+                return e;
+            }
+            continue;
+        }
         const int64_t head = (int64_t)((v - (ex + (uintptr_t)c0) % v) % v);   // columns up to alignment
         const int64_t a = c0 + head;
         if (a >= c1) break;
@@ -310,6 +330,7 @@ Knob kKnobs[] = {
     {"split_cap_finish", &g_split_cap_finish, -1, 32},
     {"split_finish_rows", &g_split_finish_rows, 0, 64},
     {"batch_rows", &g_batch_rows, 0, 8},
+    {"unaligned_wide", &g_unaligned_wide, 0, 1},
 };
 
 }  // namespace

@@ -25,7 +25,7 @@ template <int VEC, bool BF16, bool HAS_V, bool HAS_WD, int NT, int MODE>
 __global__ __launch_bounds__(64 * ((kMaxWorkers + kRowsPerWave - 1) / kRowsPerWave))
 void se_coop_kernel(const StepArgs p)
 {
-    extern __shared__ float staged[];          // [wavefronts][64 lanes][VEC]: one block sum each
+    extern __shared__ float staged[];          // [wavefronts][VEC][64 lanes]: one block sum each
     const int lane = (int)(threadIdx.x & 63u);
     const int wave = (int)(threadIdx.x >> 6);
     const int blocks = (p.m + kRowsPerWave - 1) / kRowsPerWave;     // = wavefronts of the workgroup
@@ -91,15 +91,17 @@ void se_coop_kernel(const StepArgs p)
                     for (int q = 0; q < VEC; ++q) part.a[q] = r == 0 ? out.a[q] : part.a[q] + out.a[q];
                 }
             }
-            store_f32<VEC, kPlain>((char *)(staged + ((size_t)wave * 64 + lane) * VEC), 0u, part);
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) staged[((size_t)wave * VEC + q) * 64 + lane] = part.a[q];
         }
         __syncthreads();
         if (valid) {
-            Pack<VEC> s = load_f32<VEC, kPlain>((const char *)(staged + (size_t)lane * VEC));
-            for (int b = 1; b < blocks; ++b) {
-                const Pack<VEC> t = load_f32<VEC, kPlain>((const char *)(staged + ((size_t)b * 64 + lane) * VEC));
+            Pack<VEC> s;
 #pragma unroll
-                for (int q = 0; q < VEC; ++q) s.a[q] = s.a[q] + t.a[q];
+            for (int q = 0; q < VEC; ++q) s.a[q] = staged[(size_t)q * 64 + lane];
+            for (int b = 1; b < blocks; ++b) {
+#pragma unroll
+                for (int q = 0; q < VEC; ++q) s.a[q] = s.a[q] + staged[((size_t)b * VEC + q) * 64 + lane];
             }
             Pack<VEC> mean;
 #pragma unroll

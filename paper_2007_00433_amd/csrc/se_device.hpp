@@ -96,6 +96,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+// The 4-column accessors promise the compiler 4-byte alignment only: a multi-dword global or
+// buffer access is defined for every dword-aligned address, so rows whose pitch is not a
+// multiple of 4 elements can still move 128 bits per lane (the instructions are the same).
+typedef float f32x4d __attribute__((ext_vector_type(4), aligned(4)));
+typedef unsigned short u16x4d __attribute__((ext_vector_type(4), aligned(4)));
 
 template <typename T, int NT> __device__ __forceinline__ T ld(const void *p)
 {
@@ -133,7 +138,7 @@ template <typename T> __device__ __forceinline__ void st_through(void *row, uint
 template <int N, int NT> __device__ __forceinline__ Pack<N> load_f32(const char *p)
 {
     Pack<N> r;
-    if constexpr (N == 4) { f32x4 t = ld<f32x4, NT>(p); r.a[0] = t.x; r.a[1] = t.y; r.a[2] = t.z; r.a[3] = t.w; }
+    if constexpr (N == 4) { f32x4d t = ld<f32x4d, NT>(p); r.a[0] = t.x; r.a[1] = t.y; r.a[2] = t.z; r.a[3] = t.w; }
     else if constexpr (N == 2) { f32x2 t = ld<f32x2, NT>(p); r.a[0] = t.x; r.a[1] = t.y; }
     else { r.a[0] = ld<float, NT>(p); }
     return r;
@@ -142,8 +147,8 @@ template <int N, int NT> __device__ __forceinline__ Pack<N> load_f32(const char 
 template <int N, int NT> __device__ __forceinline__ void store_f32(char *row, uint32_t off, const Pack<N> &r)
 {
     if constexpr (N == 4) {
-        const f32x4 t = {r.a[0], r.a[1], r.a[2], r.a[3]};
-        if constexpr (NT == kStreamThrough) st_through(row, off, t); else st<f32x4, NT>(row + off, t);
+        const f32x4d t = {r.a[0], r.a[1], r.a[2], r.a[3]};
+        if constexpr (NT == kStreamThrough) st_through(row, off, t); else st<f32x4d, NT>(row + off, t);
     } else if constexpr (N == 2) {
         const f32x2 t = {r.a[0], r.a[1]};
         if constexpr (NT == kStreamThrough) st_through(row, off, t); else st<f32x2, NT>(row + off, t);
@@ -156,7 +161,7 @@ template <int N, int NT> __device__ __forceinline__ Pack<N> load_bf16(const char
 {
     Pack<N> r;
     if constexpr (N == 4) {
-        u16x4 t = ld<u16x4, NT>(p);
+        u16x4d t = ld<u16x4d, NT>(p);
         r.a[0] = __uint_as_float((uint32_t)t.x << 16); r.a[1] = __uint_as_float((uint32_t)t.y << 16);
         r.a[2] = __uint_as_float((uint32_t)t.z << 16); r.a[3] = __uint_as_float((uint32_t)t.w << 16);
     } else if constexpr (N == 2) {

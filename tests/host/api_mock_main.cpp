@@ -25,9 +25,11 @@ int g_failures = 0;
 
 hipError_t record(const se::StepArgs &a, const se::LaunchShape &s, bool coop)
 {
-    const uintptr_t fa = (uintptr_t)s.vec * 4u, ga = (uintptr_t)s.vec * (s.bf16 ? 2u : 4u);
+    // 128-bit bodies: row 0 of the parameters on 16 bytes, every other row on 4 at least
+    const uintptr_t fa = s.vec == 4 ? 4u : (uintptr_t)s.vec * 4u;
+    const uintptr_t ga = s.vec == 4 ? 4u : (uintptr_t)s.vec * (s.bf16 ? 2u : 4u);
     EXPECT(s.vec == 1 || s.vec == 2 || s.vec == 4);
-    EXPECT((uintptr_t)a.x % fa == 0);
+    EXPECT((uintptr_t)a.x % ((uintptr_t)s.vec * 4u) == 0);
     EXPECT(a.pitch_bytes % fa == 0);
     if (a.v) EXPECT((uintptr_t)a.v % fa == 0);
     if (a.mode != se::kAvgOnly) { EXPECT(a.g != nullptr); EXPECT((uintptr_t)a.g % ga == 0); }
@@ -107,8 +109,10 @@ int main()
 {
     const uintptr_t X = 0x100000000ull, G = 0x200000000ull, V = 0x300000000ull;
     int calls = 0;
+    for (int wide = 0; wide < 2; ++wide)
     for (int sx = 0; sx < 4; ++sx) for (int sg = 0; sg < 4; ++sg) for (int sv = 0; sv < 4; ++sv)
     for (int bf16 = 0; bf16 < 2; ++bf16) for (int64_t pitch : {1, 2, 3, 4, 5, 63, 64, 66, 257, 4096, 4099}) {
+        EXPECT(se_set_tuning("unaligned_wide", wide) == SE_OK);
         int64_t offs[4] = {0, pitch / 3, pitch / 3 + (pitch > 7 ? 5 : 0), pitch};
         float *x = (float *)(X + 4u * sx);
         void *g = (void *)(G + (bf16 ? 2u : 4u) * sg);
@@ -128,6 +132,19 @@ int main()
         EXPECT(se_global_average(x, offs, 3, 16, nullptr) == SE_OK);
         expect_exact_cover(from, (uintptr_t)x, 0, pitch);
         EXPECT(se_ring_step(x, (const float *)(G + 4u * sg), v, offs, 3, 16, 0.1f, 0.9f, nullptr) == SE_OK);
+    }
+    // rows that are only 4-byte aligned: a 128-bit body with at most 3 scalar columns on either side
+    {
+        int64_t offs[2] = {0, 25557033};
+        for (int bf16 = 0; bf16 < 2; ++bf16) {
+            const size_t from = g_recs.size();
+            EXPECT(se_step_ex((float *)(X + 4u), (const void *)G, bf16, (float *)(V + 8u), offs, 1, 0, 1, 16, 4, 0,
+                              0.1f, 0.9f, 0.0f, 0u, nullptr) == SE_OK);
+            uint64_t wide_cols = 0;
+            for (size_t i = from; i < g_recs.size(); ++i) if (g_recs[i].vec == 4) wide_cols += g_recs[i].cols;
+            if (bf16) EXPECT(wide_cols == 0);                 // odd pitch: bf16 rows start on odd 2-byte addresses
+            else EXPECT(wide_cols >= 25557033u - 6u);
+        }
     }
     // the aligned, padded case is a single 128-bit launch
     {

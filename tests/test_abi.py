@@ -59,13 +59,14 @@ def test_seed_and_tuning_state():
     se.se_set_seed(12345678901234567890)
     assert se.se_get_seed() == 12345678901234567890
     se.se_set_seed(0)
-    assert len(se.TUNING_KNOBS) == 12
+    assert len(se.TUNING_KNOBS) == 13
     for name, good, bad in (("nontemporal", 0, 3),
                             ("max_blocks_per_cu", 2, 33), ("cooperative", 1, -1),
                             ("cache_resident_mib", 0, -1), ("coop_tiles", 3, -1),
                             ("split", 0, 2), ("split_scratch_mib", 16, 0), ("split_sub_tiles", 64, -1),
                             ("split_cap_reduce", 3, 33), ("split_cap_finish", 0, -2),
-                            ("split_finish_rows", 16, 65), ("batch_rows", 2, 9)):
+                            ("split_finish_rows", 16, 65), ("batch_rows", 2, 9),
+                            ("unaligned_wide", 0, 2)):
         assert name in se.TUNING_KNOBS
         old = se.se_get_tuning(name)
         se.se_set_tuning(name, good)

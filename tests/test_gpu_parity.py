@@ -96,8 +96,9 @@ class Case:
     narrower access paths) and a host mirror for the oracle."""
 
     def __init__(self, n, ncols, pitch=None, use_v=True, dtype="f32", shift=0, seed=0,
-                 param_std=0.05, v_std=0.0, distinct_rows=False):
+                 param_std=0.05, v_std=0.0, distinct_rows=False, shifts=None):
         self.n, self.ncols, self.dtype = n, ncols, dtype
+        self.shifts = shifts                    # element shifts of (params, grads, momentum), else `shift` for all
         self.pitch = ncols if pitch is None else pitch
         self.seed = seed
         self.hx = wl.host_params(n, ncols, param_std, seed, self.pitch)
@@ -109,19 +110,20 @@ class Case:
             if v_std:
                 self.hv[:, :ncols] = wl.host_grads(n, ncols, v_std, seed, 10 ** 6 + 1)[:, :ncols]
         self.shift = shift
-        self.dx = self._dev(self.hx, torch.float32)
-        self.dv = self._dev(self.hv, torch.float32) if use_v else None
+        self.dx = self._dev(self.hx, torch.float32, 0)
+        self.dv = self._dev(self.hv, torch.float32, 2) if use_v else None
         self.dg = None
 
-    def _dev(self, host, tdtype):
+    def _dev(self, host, tdtype, which):
+        shift = self.shifts[which] if self.shifts else self.shift
         flat = torch.empty(host.size + 8, dtype=tdtype, device="cuda")
-        view = flat[self.shift:self.shift + host.size]
+        view = flat[shift:shift + host.size]
         view.copy_(torch.from_numpy(host.reshape(-1).view(np.int16 if host.dtype == np.uint16 else host.dtype)))
         return view
 
     def grads(self, it, std):
         hg = wl.host_grads(self.n, self.ncols, std, self.seed, it, self.dtype, self.pitch)
-        self.dg = self._dev(hg, torch.int16 if self.dtype == "bf16" else torch.float32)
+        self.dg = self._dev(hg, torch.int16 if self.dtype == "bf16" else torch.float32, 1)
         return hg
 
     def offsets(self, sizes=None):
@@ -223,6 +225,45 @@ def test_misaligned_base_addresses(shift, dtype):
     case = Case(4, 70000, pitch=70000, dtype=dtype, shift=shift, distinct_rows=True, v_std=0.01)
     run_sesgd(case, 2, 2, 0.1, 0.9, 1e-2)
     case.check(f"long rows, shift {shift} {dtype}")
+
+
+@pytest.mark.parametrize("wide", [1, 0])
+def test_rows_that_share_only_four_byte_alignment(wide):
+    """Pitches that are no multiple of 4 elements and buffers at different offsets from a 16-byte
+    boundary: 128-bit accesses on 4-byte aligned rows (the default), or the 64- and 32-bit bodies
+    (unaligned_wide = 0); plain and streaming policies, every mode, split form included."""
+    old = {k: se.se_get_tuning(k) for k in se.TUNING_KNOBS}
+    try:
+        se.se_set_tuning("unaligned_wide", wide)
+        for resident in (512, 0):
+            se.se_set_tuning("cache_resident_mib", resident)
+            for ncols, shifts, dtype in [(1031, (0, 0, 0), "f32"), (70001, (1, 2, 3), "f32"), (4098, (0, 2, 1), "bf16"),
+                                         (4099, (0, 1, 0), "bf16"), (5000, (3, 0, 0), "f32"), (5000, (0, 3, 2), "bf16"),
+                                         (262, (2, 1, 0), "f32"), (9, (1, 0, 2), "f32")]:
+                what = f"wide {wide} resident {resident} cols {ncols} shifts {shifts} {dtype}"
+                say(what)
+                case = Case(8, ncols, dtype=dtype, shifts=shifts, distinct_rows=True, v_std=0.01)
+                run_sesgd(case, 4, 2, 0.1, 0.9, 1e-2)
+                case.check(what)
+                run_ring(case, 2, 0.1, 0.9, 1e-2)
+                case.check(what + " ring")
+                se.se_global_average(case.dx, case.offsets(), 8)
+                oracle.global_average(case.hx)
+                case.check(what + " global average")
+            # groups of more than 8 rows, one launch and split form
+            for split in (0, 1):
+                se.se_set_tuning("split", split)
+                what = f"wide {wide} resident {resident} split {split}, 32 workers in groups of 16"
+                say(what)
+                case = Case(32, 70003, shifts=(1, 3, 2), distinct_rows=True, v_std=0.01)
+                run_sesgd(case, 16, 2, 0.1, 0.9, 1e-2)
+                case.check(what)
+                run_ring(case, 1, 0.1, 0.9, 1e-2)
+                case.check(what + " ring")
+            se.se_set_tuning("split", old["split"])
+    finally:
+        for k, val in old.items():
+            se.se_set_tuning(k, val)
 
 
 @pytest.fixture
