@@ -128,6 +128,54 @@ int auto_blocks_per_cu(const Job &j, int batch, int vec)
     return cap < 2 ? 2 : cap > 24 ? 24 : cap;
 }
 
+// Shape of the split form for one range of columns.  False when its intermediate buffer cannot
+// be had (the stream is being captured into a graph, or the allocation failed): the caller then
+// launches the one-launch form.
+bool split_shape(const Job &j, const se::StepArgs &a, se::SplitShape *out)
+{
+    const uint32_t nb = (uint32_t)((j.m + se::kSumBlock - 1) / se::kSumBlock);
+    const uint32_t slots = j.mode == se::kSesgd ? (uint32_t)a.k * nb : (uint32_t)a.k;
+    se::SplitShape sh;
+    // Sub-chunks of 4096 tiles (4 MiB of every row) measured best when one mean gradient is
+    // re-read per row, 256-2048 tiles alike and 4096 5 % slower when 8 block sums are.
+    uint64_t sub_target = (uint64_t)g_split_sub_tiles.load() / 8u * 8u;
+    if (sub_target == 0) sub_target = j.mode == se::kSesgd ? 2048u : 4096u;
+    // Chunks as large as the buffer allows, all of the same size, each cut into sub-chunks of
+    // the same size (a short last sub-chunk would switch rows every few tiles).
+    const uint64_t budget = (uint64_t)g_split_scratch_mib.load() << 20;
+    uint64_t max_chunk = budget / ((uint64_t)slots * 1024u);         // 1 KiB per slot and tile
+    if (max_chunk < 8u) max_chunk = 8u;
+    const uint64_t all = ((uint64_t)a.tiles + 7u) / 8u * 8u;
+    const uint64_t nchunks = (all + max_chunk - 1u) / max_chunk;
+    const uint64_t chunk_target = (all + nchunks - 1u) / nchunks;
+    const uint64_t nsub = (chunk_target + sub_target - 1u) / sub_target;
+    sh.sub_tiles = (uint32_t)(((chunk_target + nsub - 1u) / nsub + 7u) / 8u * 8u);
+    const uint64_t chunk = (uint64_t)sh.sub_tiles * nsub;
+    sh.chunk_tiles = (uint32_t)chunk;
+    sh.scratch = se::split_scratch(j.stream, (size_t)(chunk * slots * 1024u));
+    if (!sh.scratch) return false;
+    int fr = g_split_finish_rows.load();
+    if (j.mode == se::kGradAvg) fr = fr >= 4 ? 4 : fr >= 2 ? 2 : 1;
+    else if (j.mode == se::kAvgOnly) fr = fr < 1 ? 1 : fr;
+    else fr = fr < 8 ? 8 : fr / 8 * 8;
+    sh.finish_rows = fr;
+    sh.reduce_batch = g_batch_rows.load() > 0 ? g_batch_rows.load() : 1;
+    // Resident workgroups per CU, from sweeps on the ResNet-50, VGG-16 and BERT shapes: the
+    // mean-gradient pass has 8 KiB or less in flight per wavefront and wants 12 or more, the
+    // one-row update 24; the 8-row SESGD pass, walked one row at a time like the single-wavefront
+    // form, 7 (10 with bf16 gradients; all 8 rows at once with 4 to 6 workgroups measured 1-4 %
+    // slower), the pass that writes the mean 16.  Without a momentum buffer a row is a third
+    // shorter: twice as many in the 8-row pass and 8 in the pass that writes the mean (6.19
+    // against 5.45 TB/s), 32 in the one-row update.
+    int cr = g_split_cap_reduce.load(), cf = g_split_cap_finish.load();
+    if (cr < 0) cr = j.mode != se::kSesgd ? (j.v ? 12 : 10) : (j.grad_bytes == 2 ? 10 : 7) * (j.v ? 1 : 2);
+    if (cf < 0) cf = j.mode != se::kSesgd ? (j.v ? 24 : 32) : (j.v ? 16 : 8);
+    sh.lds_reduce = cr > 0 ? (se::kLdsPerCu / (uint32_t)cr) & ~1023u : 0u;
+    sh.lds_finish = cf > 0 ? (se::kLdsPerCu / (uint32_t)cf) & ~1023u : 0u;
+    *out = sh;
+    return true;
+}
+
 // One launch over columns [c0, c1) with `vec` columns per lane; (c1 - c0) % vec == 0 and every
 // row of every buffer is vec-aligned at column c0 (for vec == 4, 4-byte alignment of the other
 // rows is enough when row 0 of the parameters is 16-byte aligned there).
@@ -202,47 +250,8 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
                             (uint64_t)j.n * (uint64_t)(c1 - c0) * per_elem >= ((uint64_t)1 << 31);
     if (vec == 4 && streams && j.m > se::kSumBlock && coop <= 0 &&
         (split > 0 || (split < 0 && split_pays))) {
-        const uint32_t nb = (uint32_t)((j.m + se::kSumBlock - 1) / se::kSumBlock);
-        const uint32_t slots = j.mode == se::kSesgd ? (uint32_t)a.k * nb : (uint32_t)a.k;
         se::SplitShape sh;
-        // Sub-chunks of 4096 tiles (4 MiB of every row) measured best when one mean gradient is
-        // re-read per row, 256-2048 tiles alike and 4096 5 % slower when 8 block sums are.
-        uint64_t sub_target = (uint64_t)g_split_sub_tiles.load() / 8u * 8u;
-        if (sub_target == 0) sub_target = j.mode == se::kSesgd ? 2048u : 4096u;
-        // Chunks as large as the buffer allows, all of the same size, each cut into sub-chunks of
-        // the same size (a short last sub-chunk would switch rows every few tiles).
-        const uint64_t budget = (uint64_t)g_split_scratch_mib.load() << 20;
-        uint64_t max_chunk = budget / ((uint64_t)slots * 1024u);         // 1 KiB per slot and tile
-        if (max_chunk < 8u) max_chunk = 8u;
-        const uint64_t all = ((uint64_t)a.tiles + 7u) / 8u * 8u;
-        const uint64_t nchunks = (all + max_chunk - 1u) / max_chunk;
-        const uint64_t chunk_target = (all + nchunks - 1u) / nchunks;
-        const uint64_t nsub = (chunk_target + sub_target - 1u) / sub_target;
-        sh.sub_tiles = (uint32_t)(((chunk_target + nsub - 1u) / nsub + 7u) / 8u * 8u);
-        const uint64_t chunk = (uint64_t)sh.sub_tiles * nsub;
-        sh.chunk_tiles = (uint32_t)chunk;
-        sh.scratch = se::split_scratch(j.stream, (size_t)(chunk * slots * 1024u));
-        if (sh.scratch) {
-            int fr = g_split_finish_rows.load();
-            if (j.mode == se::kGradAvg) fr = fr >= 4 ? 4 : fr >= 2 ? 2 : 1;
-            else if (j.mode == se::kAvgOnly) fr = fr < 1 ? 1 : fr;
-            else fr = fr < 8 ? 8 : fr / 8 * 8;
-            sh.finish_rows = fr;
-            sh.reduce_batch = g_batch_rows.load() > 0 ? g_batch_rows.load() : 1;
-            // Resident workgroups per CU, from sweeps on the ResNet-50, VGG-16 and BERT shapes:
-            // the mean-gradient pass has 8 KiB or less in flight per wavefront and wants 12 or
-            // more, the one-row update 24; the 8-row SESGD pass, walked one row at a time like the
-            // single-wavefront form, 7 (10 with bf16 gradients; all 8 rows at once with 4 to 6
-            // workgroups measured 1-4 % slower), the pass that writes the mean 16.  Without a
-            // momentum buffer a row is a third shorter: twice as many in the 8-row pass and 8 in the
-            // pass that writes the mean (6.19 against 5.45 TB/s), 32 in the one-row update.
-            int cr = g_split_cap_reduce.load(), cf = g_split_cap_finish.load();
-            if (cr < 0) cr = j.mode != se::kSesgd ? (j.v ? 12 : 10) : (j.grad_bytes == 2 ? 10 : 7) * (j.v ? 1 : 2);
-            if (cf < 0) cf = j.mode != se::kSesgd ? (j.v ? 24 : 32) : (j.v ? 16 : 8);
-            sh.lds_reduce = cr > 0 ? (se::kLdsPerCu / (uint32_t)cr) & ~1023u : 0u;
-            sh.lds_finish = cf > 0 ? (se::kLdsPerCu / (uint32_t)cf) & ~1023u : 0u;
-            return se::launch_split(a, s, sh, j.stream);
-        }
+        if (split_shape(j, a, &sh)) return se::launch_split(a, s, sh, j.stream);
     }
     if (use_coop) return se::launch_coop(a, s, j.stream);
     return se::launch_step(a, s, j.stream);
