@@ -59,17 +59,21 @@ int se_calib_oneway(void *dst, const void *src, int64_t nbytes, int direction, v
  *                         0 = always stream
  *   "split"               two-launch form for reductions over more than 8 rows (see sesgd.h,
  *                         "Device memory of the library's own"): 1 whenever the 128-bit path
- *                         applies, 0 never, -1 (default) when a launch moves 1 GiB or more and
- *                         the mode is not the plain parameter average
+ *                         applies, 0 never, -1 (default) when a launch moves 2 GiB or more
+ *                         (3 GiB for the plain parameter average)
  *   "split_scratch_mib"   size of that form's buffer per (device, stream), default 128
  *   "split_sub_tiles"     tiles of 64 lane-columns per sub-chunk of its second launch; 0 (default)
  *                         = 4096 when gradients are averaged, 2048 otherwise
  *   "split_cap_reduce", "split_cap_finish"   resident workgroups per compute unit of its first
  *                         and second launch; 0 = no cap; -1 (default) = 12 and 24 when gradients
  *                         are averaged, else 7 (10 with bf16 gradients) and 16; without a
- *                         momentum buffer 10 and 32, else twice as many and 8
+ *                         momentum buffer 10 and 32, else twice as many and 8; the plain
+ *                         parameter average 6, and 48 (64 beyond 32 workers) divided by the rows
+ *                         per wavefront of the second launch
  *   "split_finish_rows"   rows per wavefront of its second launch: 1, 2 or 4 when gradients are
- *                         averaged, a multiple of 8 otherwise; 0 (default) = 1 and 8
+ *                         averaged (default 1); a multiple of 8 for the SESGD update (default 8);
+ *                         any number for the plain parameter average (default an eighth of the
+ *                         workers, 2 to 8)
  * Returns SE_ERR_ARG for an unknown name or a value out of range. */
 int se_set_tuning(const char *name, int value);
 int se_get_tuning(const char *name);

@@ -156,7 +156,11 @@ bool split_shape(const Job &j, const se::StepArgs &a, se::SplitShape *out)
     if (!sh.scratch) return false;
     int fr = g_split_finish_rows.load();
     if (j.mode == se::kGradAvg) fr = fr >= 4 ? 4 : fr >= 2 ? 2 : 1;
-    else if (j.mode == se::kAvgOnly) fr = fr < 1 ? 1 : fr;
+    else if (j.mode == se::kAvgOnly) {
+        // rows one wavefront writes the mean to: an eighth of the group (2 to 8) measured best
+        const int eighth = (j.m + 7) / 8;
+        if (fr < 1) fr = eighth < 2 ? 2 : eighth > 8 ? 8 : eighth;
+    }
     else fr = fr < 8 ? 8 : fr / 8 * 8;
     sh.finish_rows = fr;
     sh.reduce_batch = g_batch_rows.load() > 0 ? g_batch_rows.load() : 1;
@@ -170,6 +174,16 @@ bool split_shape(const Job &j, const se::StepArgs &a, se::SplitShape *out)
     int cr = g_split_cap_reduce.load(), cf = g_split_cap_finish.load();
     if (cr < 0) cr = j.mode != se::kSesgd ? (j.v ? 12 : 10) : (j.grad_bytes == 2 ? 10 : 7) * (j.v ? 1 : 2);
     if (cf < 0) cf = j.mode != se::kSesgd ? (j.v ? 24 : 32) : (j.v ? 16 : 8);
+    if (j.mode == se::kAvgOnly) {
+        // The parameter average: 6 workgroups in the pass that adds the rows up (8 at a time); in
+        // the pass that writes the mean about 48 rows in flight per CU (64 beyond 32 workers),
+        // whatever the rows per wavefront.  9 to 64 workers: 6.25-6.6 TB/s (ResNet-50-sized rows).
+        if (g_split_cap_reduce.load() < 0) cr = 6;
+        if (g_split_cap_finish.load() < 0) {
+            cf = (j.m > 32 ? 64 : 48) / fr;
+            cf = cf < 2 ? 2 : cf > 32 ? 32 : cf;
+        }
+    }
     sh.lds_reduce = cr > 0 ? (se::kLdsPerCu / (uint32_t)cr) & ~1023u : 0u;
     sh.lds_finish = cf > 0 ? (se::kLdsPerCu / (uint32_t)cf) & ~1023u : 0u;
     *out = sh;
@@ -242,12 +256,12 @@ hipError_t launch_columns(const Job &j, int64_t c0, int64_t c1, int vec)
     // Split form: two launches per chunk of columns with an intermediate in a library-owned
     // buffer; for reductions over more than 8 rows on the 128-bit path.  Measured on MI355X it
     // beats the one-launch forms by 6-20 % for the gradient-averaging modes (the Ring-SGD
-    // baseline) and the SESGD update once a launch moves about 2 GiB, and it does not depend on
-    // where the driver happened to place the buffers; the parameter average alone is faster in
-    // one launch.
+    // baseline) and the SESGD update once a launch moves about 2 GiB, by 5-20 % for the parameter
+    // average of 16 to 64 workers from about 3 GiB, and it does not depend on where the driver
+    // happened to place the buffers.
     const int split = g_split.load();
-    const bool split_pays = j.mode != se::kAvgOnly &&
-                            (uint64_t)j.n * (uint64_t)(c1 - c0) * per_elem >= ((uint64_t)1 << 31);
+    const uint64_t launch_bytes = (uint64_t)j.n * (uint64_t)(c1 - c0) * per_elem;
+    const bool split_pays = launch_bytes >= (j.mode == se::kAvgOnly ? (uint64_t)3 << 30 : (uint64_t)1 << 31);
     if (vec == 4 && streams && j.m > se::kSumBlock && coop <= 0 &&
         (split > 0 || (split < 0 && split_pays))) {
         se::SplitShape sh;

@@ -60,9 +60,11 @@ hipError_t launch_step(const StepArgs &a, const LaunchShape &s, hipStream_t) { r
 hipError_t launch_coop(const StepArgs &a, const LaunchShape &s, hipStream_t) { return record(a, s, true); }
 static size_t g_scratch_bytes = 0;      // what the last split_scratch call asked for
 static int g_split_launches = 0;
+static SplitShape g_last_split;
 hipError_t launch_split(const StepArgs &a, const LaunchShape &s, const SplitShape &sh, hipStream_t)
 {
     ++g_split_launches;
+    g_last_split = sh;
     EXPECT(s.vec == 4 && a.m > 8 && sh.scratch != nullptr);
     // the buffer holds one 1 KiB piece per tile of a chunk and slot (group, or group and block of 8)
     const size_t slots = a.mode == se::kSesgd ? (size_t)a.k * (size_t)((a.m + 7) / 8) : (size_t)a.k;
@@ -179,6 +181,24 @@ int main()
             }
         }
         EXPECT(se::g_split_launches > before + 60);
+        // the parameter average of many workers: split from 3 GiB per call, an eighth of the
+        // workers (2 to 8 rows) per wavefront of the pass that writes the mean
+        se_set_tuning("split", -1); se_set_tuning("cache_resident_mib", 512);
+        se_set_tuning("split_sub_tiles", 0); se_set_tuning("split_scratch_mib", 128);
+        for (int n : {8, 9, 16, 24, 64}) for (int64_t pitch : {(int64_t)1 << 20, (int64_t)25558016, (int64_t)109483008}) {
+            int64_t offs[2] = {0, pitch};
+            const int launches = se::g_split_launches;
+            const size_t from = g_recs.size();
+            EXPECT(se_global_average((float *)X, offs, 1, n, nullptr) == SE_OK);
+            expect_exact_cover(from, X, 0, pitch);
+            const bool expected = n > 8 && (uint64_t)n * (uint64_t)pitch * 8u >= ((uint64_t)3 << 30);
+            EXPECT((se::g_split_launches == launches + 1) == expected);
+            if (expected) {
+                const int eighth = (n + 7) / 8;
+                EXPECT(se::g_last_split.finish_rows == (eighth < 2 ? 2 : eighth));
+                EXPECT(se::g_last_split.lds_finish > 0 && se::g_last_split.lds_reduce > 0);
+            }
+        }
         se_set_tuning("split", -1); se_set_tuning("cache_resident_mib", 512);
         se_set_tuning("split_sub_tiles", 0); se_set_tuning("split_scratch_mib", 128);
     }

@@ -795,6 +795,36 @@ def test_full_size_bert_one_group_of_64_equals_ring_sgd():
     torch.cuda.empty_cache()
 
 
+def test_full_size_global_average_of_64_workers_sampled():
+    """Algorithm 1's last line at the largest shape (64 replicas of 109 482 240 parameters, all
+    different): sampled columns against the oracle, every row identical afterwards, and the same
+    through the one-launch form."""
+    w = wl.WORKLOADS["bert_base_full"]
+    n, P = w.n, w.P
+    pitch = se.se_pitch(P)
+    offs = w.layer_offsets(pitch)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    x = torch.zeros(n, pitch, device="cuda")
+    for i in range(n):
+        x[i, :P] = torch.randn(P, device="cuda", generator=gen) * w.param_std
+    cols = torch.from_numpy(wl.sample_columns(pitch, 20000, seed=4)).cuda()
+    hx = x[:, cols].cpu().numpy().copy()
+    x1 = x.clone()
+    se.se_global_average(x, offs, n)                     # the form the library picks for this size
+    se.se_set_tuning("split", 0)
+    se.se_global_average(x1, offs, n)                    # one launch
+    torch.cuda.synchronize()
+    oracle.global_average(hx)
+    assert bit_mismatches(x[:, cols].cpu().numpy(), hx) == 0
+    assert torch.equal(x, x1)
+    for wkr in range(1, n):
+        assert torch.equal(x[0], x[wkr]), wkr
+    assert not x[:, P:].any().item()                     # padding columns stay zero
+    del x, x1
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("name", ["resnet18", "densenet121"])
 def test_full_size_other_networks_of_the_paper_sampled(name):
     """The two further networks of the paper's experiments (Sec. 4.1) at its 16 workers in 4
