@@ -37,7 +37,8 @@ int se_calib_oneway(void *dst, const void *src, int64_t nbytes, int direction, v
  *                         "cache_resident_mib"
  *   "batch_rows"          single-wavefront SESGD update: member rows whose loads are issued back
  *                         to back (1, 2, 4, 8); 0 (default) = 1 for groups up to 4, 2 up to 8, 8
- *                         beyond; all rows of a small group at once below "cache_resident_mib";
+ *                         beyond; below "cache_resident_mib" all rows of a small group at once
+ *                         and 2 at a time beyond 8;
  *                         also the rows per batch of the split form's first launch (default 1)
  *                         and of the update pass of one-launch gradient averaging (default 1,
  *                         2 for 5-8 workers with fp32 gradients)
