@@ -369,6 +369,9 @@ def main():
         _, wper = timed_steps(lambda t, stream: se.se_calib_oneway(b_buf, a_buf, nb, 2, stream), 10, 3, torch)
         out["copy_ceiling"]["read_only_gbs"] = round(nb / rper / 1e9, 1)
         out["copy_ceiling"]["write_only_gbs"] = round(nb / wper / 1e9, 1)
+        # torch's own device-to-device copy of the same buffers (on the current stream), for comparison
+        _, tper = timed_steps(lambda t, stream: b_buf.copy_(a_buf), 10, 3, torch)
+        out["copy_ceiling"]["torch_copy_gbs"] = round(2 * nb / tper / 1e9, 1)
         pool[1].normal_(0, w.grad_std)             # the writer left a pattern behind
     # Context only (other hardware, end-to-end training, not this path's metric): what the
     # paper reports, and its own communication-time model evaluated on this layer list.
