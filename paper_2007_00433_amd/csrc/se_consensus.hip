@@ -113,15 +113,16 @@ static hipError_t launch_part(const float *x, uint64_t pitch_elems, uint64_t nco
     return hipGetLastError();
 }
 
-// Columns [0, ncols) of n rows of pitch_elems floats: scalar head up to 16-byte alignment,
-// 128-bit body, scalar tail; all three add into the same two doubles.
+// Columns [0, ncols) of n rows of pitch_elems floats: scalar head up to 16-byte alignment of
+// row 0, 128-bit body, scalar tail; all three add into the same two doubles.  The other rows
+// need not be 16-byte aligned (any pitch): a multi-dword global load is defined for every
+// 4-byte aligned address, and the 4-column accessor promises the compiler no more than that.
 hipError_t launch_consensus(const float *x, uint64_t pitch_elems, uint64_t ncols, int n,
                             double *out_dev, hipStream_t stream)
 {
     hipLaunchKernelGGL(se_clear2_kernel, dim3(1), dim3(1), 0, stream, out_dev);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || ncols == 0) return e;
-    if (pitch_elems % 4u != 0) return launch_part<1>(x, pitch_elems, ncols, n, out_dev, stream);
     uint64_t head = (4u - ((uintptr_t)x / 4u) % 4u) % 4u;
     if (head > ncols) head = ncols;
     const uint64_t body = (ncols - head) / 4u * 4u;

@@ -915,8 +915,8 @@ def test_global_average(coop):
 
 def test_consensus_diagnostics():
     out = torch.full((2,), 7.0, dtype=torch.float64, device="cuda")
-    # (n, columns, pitch, element shift of the base): unaligned rows take the 32-bit path,
-    # aligned pitches the 128-bit body with scalar head and tail columns
+    # (n, columns, pitch, element shift of the base): odd pitches (rows that are only 4-byte
+    # aligned) and aligned ones, with scalar head and tail columns around the 128-bit body
     for n, ncols, pitch, shift in [(16, 100003, None, 0), (64, 777, None, 0), (3, 1, None, 0),
                                    (1, 50, None, 0), (16, 100003, 100004, 0), (16, 70001, 70004, 1),
                                    (9, 70002, 70004, 2), (64, 33333, 33336, 3), (17, 2, 4, 3),
