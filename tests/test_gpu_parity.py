@@ -889,6 +889,37 @@ def test_step_ex_layer_ranges_with_misaligned_boundaries():
     case.check("middle range only")
 
 
+def test_empty_layers_and_empty_models_on_the_device():
+    """Degenerate inputs: layers of zero elements between real ones, an empty layer range, and a
+    model of zero parameters launch nothing wrong and leave every byte alone where nothing is
+    to be done."""
+    sizes = [0, 5, 0, 0, 300, 0, 1027, 0]
+    n, m = 8, 4
+    case = Case(n, sum(sizes), distinct_rows=True, v_std=0.01)
+    run_sesgd(case, m, 2, 0.1, 0.9, 1e-2, sizes=sizes)
+    case.check("empty layers in between")
+    run_ring(case, 1, 0.1, 0.9, 1e-2)
+    case.check("empty layers in between, ring")
+    offs = case.offsets(sizes)
+    before_x, before_v = case.dx.clone(), case.dv.clone()
+    for first, last in [(0, 1), (2, 4), (5, 6), (8, 8), (3, 3)]:          # ranges of zero columns
+        se.se_step_ex(case.dx, case.dg, case.dv, offs, n, m, 5, 0.1, 0.9, 1e-4, 0, first_layer=first, last_layer=last)
+        se.se_step_ex(case.dx, case.dg, case.dv, offs, n, n, 5, 0.1, 0.9, 0.0, GA, first_layer=first, last_layer=last)
+    torch.cuda.synchronize()
+    assert torch.equal(case.dx, before_x) and torch.equal(case.dv, before_v)
+    # zero parameters per worker: every call is a no-op that reports success
+    x = torch.full((16,), 3.0, device="cuda"); g = torch.full((16,), 5.0, device="cuda"); v = torch.full((16,), 7.0, device="cuda")
+    out = torch.full((2,), 9.0, dtype=torch.float64, device="cuda")
+    for offs0, layers in (([0], 0), ([0, 0, 0], 2)):
+        assert se.se_step_raw("se_step", x, g, v, offs0, layers, 4, 2, 0, 0.1, 0.9, None) == se.SE_OK
+        assert se.se_ring_step_raw("se_ring_step", x, g, v, offs0, layers, 4, 0.1, 0.9, None) == se.SE_OK
+    se.se_global_average(x, [0, 0], 4)
+    se.se_consensus(x, [0, 0], 4, out)
+    torch.cuda.synchronize()
+    assert (x == 3.0).all() and (g == 5.0).all() and (v == 7.0).all()
+    assert out[0].item() == 0.0 and out[1].item() == 0.0          # sums over nothing
+
+
 def test_local_sesgd_schedule():
     """Local-SESGD (Sec. 4.1 baselines): synchronise every second iteration only; the
     iterations in between are calls with group_size = 1."""
