@@ -732,6 +732,41 @@ def test_full_size_resnet50_every_element_50_iterations():
     assert not x[:, P:].any() and not v[:, P:].any()
 
 
+def test_full_size_resnet50_ring_and_global_average_every_element():
+    """The Ring-SGD baseline (split form at this size) for 5 iterations from 16 different
+    replicas, then Algorithm 1's final global average (split form too): EVERY element of params
+    and momentum against the oracle, bit for bit."""
+    w = wl.WORKLOADS["resnet50"]
+    n, P = w.n, w.P
+    pitch = se.se_pitch(P)
+    offs = w.layer_offsets(pitch)
+    threads = len(os.sched_getaffinity(0))
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(8765)
+    x = torch.zeros(n, pitch, device="cuda")
+    x[:, :P] = torch.randn(n, P, device="cuda", generator=gen) * w.param_std
+    v = torch.zeros(n, pitch, device="cuda")
+    g = torch.zeros(n, pitch, device="cuda")
+    hx_t = torch.empty(n, pitch, pin_memory=True); hx_t.copy_(x)
+    hv_t = torch.zeros(n, pitch, pin_memory=True)
+    hg_t = torch.empty(n, pitch, pin_memory=True)
+    hx, hv, hg = hx_t.numpy(), hv_t.numpy(), hg_t.numpy()
+    for t in range(5):
+        g[:, :P] = torch.randn(n, P, device="cuda", generator=gen) * w.grad_std
+        hg_t.copy_(g)
+        se.se_ring_step(x, g, v, offs, n, w.lr, w.mu)
+        oracle.step_threaded(hx, hg, hv, n, t, w.lr, w.mu, threads=threads, ring=True)
+    torch.cuda.synchronize()
+    assert bit_mismatches(x.cpu().numpy(), hx) == 0, "params after the ring steps"
+    assert bit_mismatches(v.cpu().numpy(), hv) == 0, "momentum after the ring steps"
+    assert not torch.equal(x[0], x[1])                    # the replicas still differ
+    se.se_global_average(x, offs, n)
+    oracle.global_average(hx)
+    torch.cuda.synchronize()
+    assert bit_mismatches(x.cpu().numpy(), hx) == 0, "params after the global average"
+    assert not x[:, P:].any() and not v[:, P:].any()
+
+
 def test_full_size_resnet50_ring_sampled():
     _full_size_sampled("resnet50", 10, ring=True)
 
