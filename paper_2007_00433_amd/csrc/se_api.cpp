@@ -24,9 +24,9 @@ std::atomic<int> g_split_scratch_mib{128}; // size of the split form's intermedi
 std::atomic<int> g_split_sub_tiles{0};    // tiles per sub-chunk of the split form's finish launch (0 = by mode)
 std::atomic<int> g_split_cap_reduce{-1};  // resident workgroups per CU of the two launches (0 = no cap, -1 = default)
 std::atomic<int> g_split_cap_finish{-1};
-std::atomic<int> g_batch_rows{0};            // single-wavefront SESGD update: rows per batch of loads (0 = by group size)
-std::atomic<int> g_unaligned_wide{1};        // 128-bit accesses also for rows that are only 4-byte aligned
 std::atomic<int> g_split_finish_rows{0};  // rows per wavefront of the finish launch (0 = default)
+std::atomic<int> g_batch_rows{0};         // member rows whose loads are issued back to back (0 = chosen per launch)
+std::atomic<int> g_unaligned_wide{1};     // 128-bit accesses also for rows that are only 4-byte aligned
 
 thread_local char t_last_error[256] = "";
 
