@@ -468,12 +468,7 @@ def main():
 
         # Buckets, as data-parallel frameworks cut their gradient exchange: consecutive tensors
         # (back to front) are stepped together once they add up to 1 Mi elements or more.
-        buckets, hi, acc = [], L, 0
-        for l in range(L - 1, -1, -1):
-            acc += int(w.sizes[l])
-            if acc >= (1 << 20) or l == 0:
-                buckets.append((l, hi))
-                hi, acc = l, 0
+        buckets = se.se_layer_buckets(w.layer_offsets(), 1 << 20)
 
         def launch_buckets(t, stream):
             for first, last in buckets:

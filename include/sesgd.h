@@ -197,6 +197,24 @@ int se_comm_model(const int64_t *layer_offsets, int num_layers, int elem_bytes, 
                   double bandwidth, double latency, double *ring_seconds, double *sesgd_seconds,
                   int64_t *ring_handshakes, int64_t *sesgd_handshakes);
 
+/*
+ * Host-only helper for stepping a model in layer ranges while backward still runs (Sec. 2.1:
+ * the last layer's gradients are ready first, and the exchange of one layer overlaps the
+ * backward pass of the layers before it).  One se_step_ex call per layer pays a launch for
+ * every small tensor (Sec. 2.3 counts the same cost in handshakes); this cuts the layers, back
+ * to front, into consecutive ranges of at least min_elements elements each.  Layers are never
+ * split; the front-most range takes what is left and may be smaller.
+ *   first_layer [host, out, `capacity` ints]  first layer of each range in stepping order (back
+ *                to front): range i covers layers [first_layer[i], end_i) with end_0 =
+ *                num_layers and end_i = first_layer[i-1]; pass them to se_step_ex as
+ *                first_layer / last_layer
+ *   num_ranges  [host, out]  number of ranges (0 for a model without layers)
+ * When `capacity` is too small, *num_ranges is set, first_layer is left alone and SE_ERR_ARG is
+ * returned (num_layers entries always suffice).  Touches no device.
+ */
+int se_layer_buckets(const int64_t *layer_offsets, int num_layers, int64_t min_elements,
+                     int32_t *first_layer, int capacity, int *num_ranges);
+
 /* The shared random seed of Algorithm 1 (process-wide, default 0).  Read at call time by
  * se_plan, se_plan_device and se_step. */
 int      se_set_seed(uint64_t seed);

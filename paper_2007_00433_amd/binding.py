@@ -28,7 +28,7 @@ SE_MAX_WORKERS = 64
 EXPORTS = ("se_plan", "se_plan_noalloc", "se_plan_device", "se_step", "se_step_bf16g", "se_ring_step",
            "se_ring_step_bf16g", "se_set_seed", "se_get_seed", "se_pitch", "se_step_bytes",
            "se_set_tuning", "se_get_tuning", "se_strerror", "se_last_error", "se_calib_copy", "se_calib_oneway",
-           "se_step_ex", "se_global_average", "se_consensus", "se_comm_model")
+           "se_step_ex", "se_global_average", "se_consensus", "se_comm_model", "se_layer_buckets")
 
 
 SE_FLAG_GRAD_AVG = 1
@@ -94,6 +94,8 @@ def _load() -> ctypes.CDLL:
     lib.se_comm_model.restype = i32
     lib.se_comm_model.argtypes = [vp, i32, i32, i32, i32, ctypes.c_double, ctypes.c_double,
                                   vp, vp, vp, vp]
+    lib.se_layer_buckets.restype = i32
+    lib.se_layer_buckets.argtypes = [vp, i32, i64, vp, i32, vp]
     lib.se_calib_copy.restype = i32
     lib.se_calib_copy.argtypes = [vp, vp, i64, vp]
     lib.se_calib_oneway.restype = i32
@@ -337,6 +339,24 @@ def se_consensus(params, layer_offsets, n: int, out_dev, stream=None) -> None:
     offs = _offsets(layer_offsets)
     check(lib.se_consensus(_rows(params, n, int(offs[-1]), 4, "params"), offs.ctypes.data,
                            len(offs) - 1, n, _rows(out_dev, 1, 2, 8, "out_dev"), _stream(stream)))
+
+
+def se_layer_buckets_raw(layer_offsets, num_layers, min_elements, first_layer_ptr, capacity, num_ranges_ptr) -> int:
+    offs = None if layer_offsets is None else _offsets(layer_offsets)
+    return int(lib.se_layer_buckets(None if offs is None else offs.ctypes.data, num_layers, min_elements,
+                                    first_layer_ptr, capacity, num_ranges_ptr))
+
+
+def se_layer_buckets(layer_offsets, min_elements: int) -> list:
+    """[(first_layer, last_layer), ...] in stepping order (back to front), for se_step_ex."""
+    offs = _offsets(layer_offsets)
+    L = len(offs) - 1
+    first = np.zeros(max(L, 1), np.int32)
+    count = ctypes.c_int(0)
+    check(lib.se_layer_buckets(offs.ctypes.data, L, int(min_elements), first.ctypes.data, L,
+                               ctypes.addressof(count)))
+    ends = [L] + [int(f) for f in first[:count.value]]
+    return [(int(first[i]), ends[i]) for i in range(count.value)]
 
 
 def se_comm_model(layer_offsets, elem_bytes: int, n: int, groups: int, bandwidth: float,

@@ -489,6 +489,33 @@ int se_comm_model(const int64_t *layer_offsets, int num_layers, int elem_bytes, 
     return SE_OK;
 }
 
+int se_layer_buckets(const int64_t *layer_offsets, int num_layers, int64_t min_elements,
+                     int32_t *first_layer, int capacity, int *num_ranges)
+{
+    if (num_layers < 0 || min_elements < 1 || capacity < 0) return SE_ERR_ARG;
+    if (!layer_offsets || !num_ranges || (capacity > 0 && !first_layer)) return SE_ERR_NULL;
+    if (layer_offsets[0] != 0) return SE_ERR_LAYOUT;
+    for (int l = 0; l < num_layers; ++l)
+        if (layer_offsets[l + 1] < layer_offsets[l]) return SE_ERR_LAYOUT;
+    // back to front: a range is closed as soon as it holds min_elements, the front-most range
+    // takes what is left; first a count, so that nothing is written when it does not fit
+    for (int pass = 0; pass < 2; ++pass) {
+        int count = 0, end = num_layers;
+        for (int l = num_layers - 1; l >= 0; --l) {
+            if (layer_offsets[end] - layer_offsets[l] >= min_elements || l == 0) {
+                if (pass == 1) first_layer[count] = (int32_t)l;
+                ++count;
+                end = l;
+            }
+        }
+        if (pass == 0) {
+            *num_ranges = count;
+            if (count > capacity) return SE_ERR_ARG;
+        }
+    }
+    return SE_OK;
+}
+
 int se_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream)
 {
     if (nbytes < 0) return SE_ERR_ARG;

@@ -196,6 +196,60 @@ def test_comm_model_matches_the_oracle_and_the_paper():
                                 None, None, None, None) == se.SE_OK
 
 
+def test_layer_buckets_cover_the_model_back_to_front():
+    """Host-only helper for layer-range stepping (Sec. 2.1): ranges are consecutive, run from the
+    last layer to the first, cover every layer once, hold at least min_elements each except the
+    front-most one, and are as small as that allows (dropping the first layer of a range would
+    take it below min_elements)."""
+    import ctypes
+    from paper_2007_00433_amd import workloads as wl
+    rng = np.random.default_rng(3)
+    models = [list(w.sizes) for w in wl.WORKLOADS.values()]
+    models += [list(rng.integers(0, 5000, size=int(L))) for L in rng.integers(1, 60, size=30)]
+    models += [[0, 0, 0], [7], [0], [5, 0, 0, 5], []]
+    for sizes in models:
+        offs = np.concatenate([[0], np.cumsum(np.asarray(sizes, np.int64))]).astype(np.int64)
+        L = len(sizes)
+        for min_elems in (1, 100, 4096, 1 << 20, 1 << 40):
+            ranges = se.se_layer_buckets(offs, min_elems)
+            if L == 0:
+                assert ranges == []
+                continue
+            assert ranges[0][1] == L and ranges[-1][0] == 0
+            for (f0, l0), (f1, l1) in zip(ranges, ranges[1:]):
+                assert l1 == f0                                   # consecutive, back to front
+            for q, (f, l) in enumerate(ranges):
+                assert 0 <= f < l <= L
+                size = int(offs[l] - offs[f])
+                if q < len(ranges) - 1:
+                    assert size >= min_elems
+                    assert int(offs[l] - offs[f + 1]) < min_elems  # closed as early as possible
+            if min_elems == 1 << 40:
+                assert ranges == [(0, L)]
+    # the ResNet-50 shape in ranges of 2^20 elements: 19 calls instead of 161
+    w = wl.WORKLOADS["resnet50"]
+    assert len(se.se_layer_buckets(w.layer_offsets(), 1 << 20)) == 19
+    assert len(se.se_layer_buckets(w.layer_offsets(), 1)) == 161
+    # a hand-checked case: sizes 10, 3, 4, 20, 1 with at least 5 per range
+    assert se.se_layer_buckets([0, 10, 13, 17, 37, 38], 5) == [(3, 5), (1, 3), (0, 1)]
+    # errors: nothing is written when the ranges do not fit
+    offs = np.asarray([0, 10, 13, 17, 37, 38], np.int64)
+    first = np.full(8, -7, np.int32)
+    count = ctypes.c_int(-1)
+    cnt = ctypes.addressof(count)
+    assert se.se_layer_buckets_raw(offs, 5, 5, first.ctypes.data, 2, cnt) == se.SE_ERR_ARG
+    assert count.value == 3 and (first == -7).all()
+    assert se.se_layer_buckets_raw(offs, 5, 0, first.ctypes.data, 8, cnt) == se.SE_ERR_ARG
+    assert se.se_layer_buckets_raw(offs, -1, 5, first.ctypes.data, 8, cnt) == se.SE_ERR_ARG
+    assert se.se_layer_buckets_raw(None, 5, 5, first.ctypes.data, 8, cnt) == se.SE_ERR_NULL
+    assert se.se_layer_buckets_raw(offs, 5, 5, None, 8, cnt) == se.SE_ERR_NULL
+    assert se.se_layer_buckets_raw(offs, 5, 5, first.ctypes.data, 8, None) == se.SE_ERR_NULL
+    assert se.se_layer_buckets_raw(np.asarray([0, 5, 3], np.int64), 2, 5, first.ctypes.data, 8, cnt) == se.SE_ERR_LAYOUT
+    assert (first == -7).all()
+    assert se.se_layer_buckets_raw(offs, 5, 5, first.ctypes.data, 3, cnt) == se.SE_OK
+    assert list(first[:3]) == [3, 1, 0] and (first[3:] == -7).all()
+
+
 def test_binding_checks_tensors_before_taking_their_address():
     """The checked wrappers refuse tensors the kernels would run past or misread (no GPU needed:
     a host tensor is refused first of all)."""

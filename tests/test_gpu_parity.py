@@ -916,6 +916,19 @@ def test_step_ex_layer_ranges_with_misaligned_boundaries():
         full.check("layer ranges: full step")
         torch.cuda.synchronize()
         assert torch.equal(full.dx, parts.dx) and torch.equal(full.dv, parts.dv)
+    # the ranges the library proposes (at least 300 elements each, back to front) give the full step too
+    full, parts = Case(n, P, distinct_rows=True, v_std=0.01), Case(n, P, distinct_rows=True, v_std=0.01)
+    ranges = se.se_layer_buckets(offs, 300)
+    assert ranges == [(7, 9), (4, 7), (0, 4)]
+    for t in range(2):
+        hg = full.grads(t, 1e-2)
+        parts.dg = full.dg
+        se.se_step_ex(full.dx, full.dg, full.dv, offs, n, m, t, 0.1, 0.9, 0.0, 0)
+        oracle.step_ex(full.hx, hg, full.hv, m, t, 0.1, 0.9, 0.0, 0)
+        for first, last in ranges:
+            se.se_step_ex(parts.dx, parts.dg, parts.dv, offs, n, m, t, 0.1, 0.9, 0.0, 0, first_layer=first, last_layer=last)
+    full.check("layer buckets: full step")
+    assert torch.equal(full.dx, parts.dx) and torch.equal(full.dv, parts.dv)
     # a single middle range leaves the other columns alone
     case = Case(n, P, distinct_rows=True, v_std=0.01)
     hg = case.grads(0, 1e-2)
