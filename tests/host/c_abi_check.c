@@ -1,5 +1,6 @@
 /* Plain C user of the C ABI: no Python, no torch.  Allocates with the HIP runtime, runs
- * se_plan / se_step / se_ring_step / se_step_ex / se_global_average / se_consensus on a small
+ * se_plan / se_plan_noalloc / se_step / se_ring_step / se_step_ex (ranges from se_layer_buckets) /
+ * se_global_average / se_consensus on a small
  * ragged problem and compares every result with the CPU oracle (linked in from oracle/, which
  * is why this program lives with the tests).  Exit status 0 = all equal.
  * Built by __graft_entry__.build(); run by tests/test_gpu_c_abi.py on the GPU machine. */
@@ -65,6 +66,11 @@ int main(void)
             fprintf(stderr, "MISMATCH in plan, iter %d\n", t);
             ++bad;
         }
+        SECHECK(se_plan_noalloc(N, M, t, group_of, members));       /* the form that allocates nothing */
+        if (memcmp(group_of, o_group_of, sizeof group_of) || memcmp(members, o_members, sizeof members)) {
+            fprintf(stderr, "MISMATCH in plan (no allocation), iter %d\n", t);
+            ++bad;
+        }
         switch (t) {
         case 0:
             SECHECK(se_step(dx, dg, dv, offs, L, N, M, t, 0.1f, 0.9f, NULL));
@@ -74,11 +80,21 @@ int main(void)
             SECHECK(se_ring_step(dx, dg, dv, offs, L, N, 0.1f, 0.9f, NULL));
             if (oracle_ring_step(hx, hg, 0, hv, pitch, 0, pitch, N, 0.1f, 0.9f)) return 4;
             break;
-        case 2:      /* two layer ranges, weight decay */
-            SECHECK(se_step_ex(dx, dg, 0, dv, offs, L, 2, L, N, M, t, 0.1f, 0.9f, 5e-4f, 0u, NULL));
-            SECHECK(se_step_ex(dx, dg, 0, dv, offs, L, 0, 2, N, M, t, 0.1f, 0.9f, 5e-4f, 0u, NULL));
+        case 2: {    /* layer ranges of at least 1000 elements, back to front; weight decay */
+            int32_t first[L];
+            int ranges = -1, r, end = L;
+            SECHECK(se_layer_buckets(offs, L, 1000, first, L, &ranges));
+            if (ranges != 3 || first[0] != 3 || first[1] != 2 || first[2] != 0) {
+                fprintf(stderr, "MISMATCH in layer buckets: %d ranges\n", ranges);
+                ++bad;
+            }
+            for (r = 0; r < ranges; ++r) {
+                SECHECK(se_step_ex(dx, dg, 0, dv, offs, L, first[r], end, N, M, t, 0.1f, 0.9f, 5e-4f, 0u, NULL));
+                end = first[r];
+            }
             if (oracle_step_ex(hx, hg, 0, hv, pitch, 0, pitch, N, M, 42, t, 0.1f, 0.9f, 5e-4f, 0u)) return 4;
             break;
+        }
         default:     /* the uncorrected variant */
             SECHECK(se_step_ex(dx, dg, 0, dv, offs, L, 0, L, N, M, t, 0.1f, 0.9f, 0.0f, SE_FLAG_GRAD_AVG, NULL));
             if (oracle_step_ex(hx, hg, 0, hv, pitch, 0, pitch, N, M, 42, t, 0.1f, 0.9f, 0.0f, 1u)) return 4;
