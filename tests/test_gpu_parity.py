@@ -486,6 +486,37 @@ def test_split_form_for_large_groups(sub_tiles, always_streaming):
     case.check("split: layer ranges, no momentum")
 
 
+def test_split_form_on_two_streams_at_once(always_streaming):
+    """Two models stepped at the same time on two streams: the split form's intermediate buffer
+    is per stream, so neither sees the other's block sums or mean gradients.  The steps are
+    enqueued alternately without waiting in between, with different chunk sizes per model."""
+    se.se_set_tuning("split", 1)
+    se.se_set_tuning("split_scratch_mib", 1)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    a = Case(32, 90000, distinct_rows=True, v_std=0.01, seed=1)
+    b = Case(24, 50004, dtype="bf16", distinct_rows=True, v_std=0.01, seed=2)
+    offs_a, offs_b = a.offsets(), b.offsets()
+    T = 4
+    ga = [torch.from_numpy(wl.host_grads(a.n, a.ncols, 1e-2, a.seed, t)).cuda() for t in range(T)]
+    hgb = [wl.host_grads(b.n, b.ncols, 1e-2, b.seed, t, "bf16") for t in range(T)]
+    gb = [torch.from_numpy(h.view(np.int16)).cuda() for h in hgb]
+    torch.cuda.synchronize()
+    for t in range(T):
+        se.se_step(a.dx, ga[t], a.dv, offs_a, a.n, 16, t, 0.1, 0.9, s1)
+        se.se_ring_step_bf16g(b.dx, gb[t], b.dv, offs_b, b.n, 0.1, 0.9, s2)
+        se.se_ring_step(a.dx, ga[t], a.dv, offs_a, a.n, 0.1, 0.9, s1)
+        se.se_step_bf16g(b.dx, gb[t], b.dv, offs_b, b.n, 12, t, 0.1, 0.9, s2)
+    torch.cuda.synchronize()
+    for t in range(T):
+        hga = ga[t].cpu().numpy()
+        oracle.step(a.hx, hga, a.hv, 16, t, 0.1, 0.9)
+        oracle.ring_step(a.hx, hga, a.hv, 0.1, 0.9)
+        oracle.ring_step(b.hx, hgb[t], b.hv, 0.1, 0.9)
+        oracle.step(b.hx, hgb[t], b.hv, 12, t, 0.1, 0.9)
+    a.check("two streams, model a")
+    b.check("two streams, model b")
+
+
 @pytest.mark.parametrize("form", ["one launch", "lds staged", "split"])
 def test_summation_order_examples_by_hand_on_the_gpu(form, golden_dir, always_streaming):
     """The hand-evaluated sums of tests/golden/summation_order_examples.json (blocks of 8
