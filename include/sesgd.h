@@ -32,13 +32,13 @@
  *     kernel launches only (no memset), so they may be captured in a HIP graph; the first
  *     launch of each kernel variant on a device also sets a function attribute, so make one
  *     ordinary call with the same argument types before capturing.
- *   - Device memory of the library's own: reductions over more than 8 rows (se_ring_step with
- *     n > 8, group_size > 8) on large buffers run as pairs of launches that hand mean gradients
- *     or block sums over through a buffer the library allocates on first use, one per
- *     (device, stream), at most 128 MiB each by default, grown on demand and kept until the
- *     process ends.  Steps on different streams never share a buffer.  While `stream` is being
- *     captured, or when no buffer can be had, the one-launch form runs instead; results are
- *     bit-identical either way.
+ *   - Device memory of the library's own: reductions over more than 8 rows (se_ring_step and
+ *     se_global_average with n > 8, group_size > 8) on large buffers run as pairs of launches
+ *     that hand means or block sums over through a buffer the library allocates on first use,
+ *     one per (device, stream) for up to 16 such pairs, at most 128 MiB each by default, grown
+ *     on demand and kept until the process ends.  Steps on different streams never share a
+ *     buffer.  While `stream` is being captured, or when no buffer can be had, the one-launch
+ *     form runs instead; results are bit-identical either way.
  *   - fp32 arithmetic, round-to-nearest-even, denormals kept, with this fixed order per
  *     element e and group with members j_0 < j_1 < ... (ascending worker id):
  *         v'_j   = fma(mu, v_j, g_j)            (g_j if momentum == NULL)
