@@ -15,8 +15,8 @@
 //            of 8 members) does the local momentum/SGD step of its 8 rows, stores v, and stores
 //            the block's sum of x-hat.
 //   finish   kGradAvg: one wavefront per (tile, worker) updates that worker's v and x with the
-//            stored mean gradient.  kAvgOnly: one wavefront per (tile, worker) writes the stored
-//            mean into that worker's row.
+//            stored mean gradient.  kAvgOnly: one wavefront per (tile, a few workers) writes the
+//            stored mean into those workers' rows.
 //            kSesgd: one wavefront per (tile, group, block) adds the group's stored block sums
 //            left to right, scales by 1/m and writes the mean to its 8 rows.
 //
