@@ -668,7 +668,7 @@ def test_error_codes_on_the_device_box():
 
 
 # ------------------------------------------------------------------------ full size
-def _full_size_sampled(name, iters, ring=False, group_size=None):
+def _full_size_sampled(name, iters, ring=False, group_size=None, pitch=None):
     """The benchmark's launch configuration at the workload's full size, for the stated number
     of iterations.  Inputs are drawn on the device by torch (seeded); the oracle replays a
     stratified column sample exactly, because columns are independent: 96 whole 1 KiB pieces of
@@ -677,7 +677,7 @@ def _full_size_sampled(name, iters, ring=False, group_size=None):
     untouched padding stays zero."""
     w = wl.WORKLOADS[name]
     n, m, P = w.n, group_size or w.group_size, w.P
-    pitch = se.se_pitch(P)
+    pitch = pitch or se.se_pitch(P)
     offs = w.layer_offsets(pitch)
     bf16 = w.grad_dtype == "bf16"
     gen = torch.Generator(device="cuda")
@@ -897,6 +897,16 @@ def test_full_size_other_networks_of_the_paper_sampled(name):
     groups: 10 iterations of the step and of the Ring-SGD baseline at full size."""
     _full_size_sampled(name, 10)
     _full_size_sampled(name, 3, ring=True)
+
+
+def test_full_size_resnet50_rows_that_are_only_four_byte_aligned_sampled():
+    """The headline shape with a row pitch of P + 1 elements (odd: consecutive rows start 4, 8,
+    12 bytes off a 16-byte boundary): the 128-bit path for 4-byte aligned rows at full size, the
+    step, one group of 16 (split form) and the Ring-SGD baseline."""
+    P = wl.WORKLOADS["resnet50"].P
+    _full_size_sampled("resnet50", 3, pitch=P + 1)
+    _full_size_sampled("resnet50", 2, pitch=P + 1, group_size=16)
+    _full_size_sampled("resnet50", 2, pitch=P + 1, ring=True)
 
 
 @pytest.mark.parametrize("group_size", [1, 2, 16])
